@@ -1,0 +1,210 @@
+"""CPU oracle for KV-cache schedule evaluation -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes access to ``kvs_oracle.c`` (plain C, single-threaded, literal
+round-by-round stepping of the model of Section 2.1 of "Competitive
+Non-Clairvoyant KV-Cache Scheduling for LLM Inference").  Only the tests, the
+smoke check and the CPU-baseline leg of the benchmark may import this package;
+the GPU library and its Python binding never do, and this package imports
+nothing of theirs.
+
+The C file is compiled with gcc on first use (and again when the source is
+newer than the library).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kvs_oracle.c")
+_LIB = os.path.join(_HERE, "libkvs_oracle.so")
+
+SPS, SIMS = 0, 1
+MODE_GBA, MODE_GSA = 0, 1
+OK, EINVAL, EJOB_INFEASIBLE, ENOMEM = 0, 1, 2, 3
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code: int):
+        super().__init__(f"oracle status {code}")
+        self.code = code
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle into a shared library next to its source."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", tmp, _SRC]
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        i64, i32 = C.c_int64, C.c_int32
+        p32, p64, pu8 = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_uint8)
+        _lib.kvo_peak_formula.restype = i64
+        _lib.kvo_peak_formula.argtypes = [i64, i64, i64]
+        _lib.kvo_kstar.restype = i64
+        _lib.kvo_kstar.argtypes = [i64, i64, i64]
+        _lib.kvo_area.restype = i64
+        _lib.kvo_area.argtypes = [i64, i64]
+        _lib.kvo_step_runs.restype = C.c_int
+        _lib.kvo_step_runs.argtypes = [i64, p64, p64, p64, p64, p64]
+        _lib.kvo_schedule_eval.restype = C.c_int
+        _lib.kvo_schedule_eval.argtypes = [i64, p32, p32, i64, i64, i64, i64, C.c_int,
+                                           p64, p32, p64, p64, p64]
+        _lib.kvo_gba_simulate.restype = C.c_int
+        _lib.kvo_gba_simulate.argtypes = [i64, p32, p32, p32, i64, i64, i64, C.c_int, i64,
+                                          C.c_int, p64, p32, p64, p64, p64]
+        _lib.kvo_gba_simulate_batch.restype = C.c_int
+        _lib.kvo_gba_simulate_batch.argtypes = [i64, i64, i64, p32, p32, p32, i64, i64, i64,
+                                                p32, p32, p32, p32, p64, pu8, p64, p64]
+        _lib.kvo_schedule_eval_batch.restype = C.c_int
+        _lib.kvo_schedule_eval_batch.argtypes = [i64, i64, i64, p32, p32, i64, i64, i64,
+                                                 p32, p32, p32, p64, pu8, p64, p32, p64]
+        _lib.kvo_opt_perm.restype = C.c_int
+        _lib.kvo_opt_perm.argtypes = [i64, p32, i64, i64, p64]
+        _lib.kvo_opt_exact.restype = C.c_int
+        _lib.kvo_opt_exact.argtypes = [i64, p32, i64, i64, p64]
+    return _lib
+
+
+def _p32(a):
+    return None if a is None else a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _p64(a):
+    return a.ctypes.data_as(C.POINTER(C.c_int64))
+
+
+def _i32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _check(rc):
+    if rc != OK:
+        raise OracleError(rc)
+
+
+def peak_formula(k: int, tau: int, s: int) -> int:
+    return int(lib().kvo_peak_formula(k, tau, s))
+
+
+def kstar(tau: int, s: int, M: int) -> int:
+    return int(lib().kvo_kstar(tau, s, M))
+
+
+def area(o: int, s: int) -> int:
+    return int(lib().kvo_area(o, s))
+
+
+def step_runs(start, dur, s):
+    """Occupancy peak and job-steps of explicit runs (sorted by start)."""
+    start = np.ascontiguousarray(start, dtype=np.int64)
+    dur = np.ascontiguousarray(dur, dtype=np.int64)
+    s = np.ascontiguousarray(s, dtype=np.int64)
+    peak, steps = C.c_int64(), C.c_int64()
+    _check(lib().kvo_step_runs(len(start), _p64(start), _p64(dur), _p64(s),
+                               C.byref(peak), C.byref(steps)))
+    return peak.value, steps.value
+
+
+def schedule_eval(o, s, M, tau, k=0, sched=SPS):
+    """One SPS / SimS invocation on the whole sequence.  `s`: int or array."""
+    o = _i32(o)
+    s_arr = None if np.isscalar(s) else _i32(s)
+    s_scalar = int(s) if np.isscalar(s) else 0
+    peak, flow, nc, steps = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
+    feas = C.c_int32()
+    _check(lib().kvo_schedule_eval(len(o), _p32(o), _p32(s_arr), s_scalar, M, tau, k, sched,
+                                   C.byref(peak), C.byref(feas), C.byref(flow), C.byref(nc),
+                                   C.byref(steps)))
+    return dict(peak=peak.value, feasible=feas.value, flow=flow.value,
+                n_completed=nc.value, job_steps=steps.value)
+
+
+def gba_simulate(o, s, M, tau0=1, sched=SPS, k=0, mode=MODE_GBA, o_est=None):
+    """One instance at one sweep point.  `s`: int or array."""
+    o = _i32(o)
+    s_arr = None if np.isscalar(s) else _i32(s)
+    s_scalar = int(s) if np.isscalar(s) else 0
+    e = _i32(o_est)
+    peak, flow, steps, phases = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
+    feas = C.c_int32()
+    _check(lib().kvo_gba_simulate(len(o), _p32(o), _p32(s_arr), _p32(e), s_scalar, M, tau0,
+                                  sched, k, mode, C.byref(peak), C.byref(feas), C.byref(flow),
+                                  C.byref(steps), C.byref(phases)))
+    return dict(peak=peak.value, feasible=feas.value, flow=flow.value,
+                job_steps=steps.value, n_phases=phases.value)
+
+
+def gba_simulate_batch(o, s, M, points, o_est=None, i0=0, i1=None):
+    """Instances [i0, i1) of [I][n] arrays at every point (tau0, sched, k, mode).
+
+    Returns dict of arrays shaped [n_pts][i1 - i0]."""
+    o = _i32(o)
+    I, n = o.shape
+    i1 = I if i1 is None else i1
+    s_arr = None if np.isscalar(s) else _i32(s)
+    s_scalar = int(s) if np.isscalar(s) else 0
+    e = _i32(o_est)
+    pts = np.asarray(points, dtype=np.int32).reshape(-1, 4)
+    tau0, sched, k, mode = (np.ascontiguousarray(pts[:, j]) for j in range(4))
+    P, cnt = len(pts), i1 - i0
+    peak = np.zeros((P, cnt), np.int64)
+    flow = np.zeros((P, cnt), np.int64)
+    steps = np.zeros((P, cnt), np.int64)
+    feas = np.zeros((P, cnt), np.uint8)
+    _check(lib().kvo_gba_simulate_batch(i0, i1, n, _p32(o), _p32(s_arr), _p32(e), s_scalar, M,
+                                        P, _p32(tau0), _p32(sched), _p32(k), _p32(mode),
+                                        _p64(peak), feas.ctypes.data_as(C.POINTER(C.c_uint8)),
+                                        _p64(flow), _p64(steps)))
+    return dict(peak=peak, feasible=feas, flow=flow, job_steps=steps)
+
+
+def schedule_eval_batch(o, s, M, points, i0=0, i1=None):
+    """Instances [i0, i1) at every point (tau, k, sched)."""
+    o = _i32(o)
+    I, n = o.shape
+    i1 = I if i1 is None else i1
+    s_arr = None if np.isscalar(s) else _i32(s)
+    s_scalar = int(s) if np.isscalar(s) else 0
+    pts = np.asarray(points, dtype=np.int32).reshape(-1, 3)
+    tau, k, sched = (np.ascontiguousarray(pts[:, j]) for j in range(3))
+    P, cnt = len(pts), i1 - i0
+    peak = np.zeros((P, cnt), np.int64)
+    flow = np.zeros((P, cnt), np.int64)
+    steps = np.zeros((P, cnt), np.int64)
+    nc = np.zeros((P, cnt), np.int32)
+    feas = np.zeros((P, cnt), np.uint8)
+    _check(lib().kvo_schedule_eval_batch(i0, i1, n, _p32(o), _p32(s_arr), s_scalar, M, P,
+                                         _p32(tau), _p32(k), _p32(sched), _p64(peak),
+                                         feas.ctypes.data_as(C.POINTER(C.c_uint8)), _p64(flow),
+                                         _p32(nc), _p64(steps)))
+    return dict(peak=peak, feasible=feas, flow=flow, n_completed=nc, job_steps=steps)
+
+
+def opt_perm(o, s: int, M: int) -> int:
+    o = _i32(o)
+    best = C.c_int64()
+    _check(lib().kvo_opt_perm(len(o), _p32(o), s, M, C.byref(best)))
+    return best.value
+
+
+def opt_exact(o, s: int, M: int) -> int:
+    o = _i32(o)
+    best = C.c_int64()
+    _check(lib().kvo_opt_exact(len(o), _p32(o), s, M, C.byref(best)))
+    return best.value
