@@ -1,0 +1,147 @@
+#!/usr/bin/env python3
+"""Throughput of the batched schedule evaluation on one MI355X.
+
+A step is one pass of the whole hot path (classification into geometric
+batches, phase tables, start times, per-round occupancy, MemPeak, FlowTime)
+over one batch of synthetic instances at every sweep point: one call of
+kvs_gba_simulate.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` = simulated job-decode-steps per second;
+`roofline` = algorithmic HBM bytes of the evaluation kernel over its measured
+duration against the 8 TB/s peak; `cpu_baseline` = the CPU oracle timed on a
+bounded sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+CHUNK = 4096                   # instances generated and uploaded at a time
+
+
+def load_workload(w, torch, threads):
+    """Generate the whole workload on the host, chunk by chunk, into device tensors."""
+    from paper_2601_22996_amd import workloads as W
+    I, n = w.n_instances, w.n_jobs
+    dev = torch.device("cuda:0")
+    o = torch.empty((I, n), dtype=torch.int32, device=dev)
+    s = torch.empty((I, n), dtype=torch.int32, device=dev) if w.s_scalar is None else None
+    e = torch.empty((I, n), dtype=torch.int32, device=dev) if w.estimates else None
+    buf = None
+    for i0 in range(0, I, CHUNK):
+        i1 = min(I, i0 + CHUNK)
+        buf = W.generate(w, i0, i1, threads=threads, out=buf)
+        o[i0:i1].copy_(torch.from_numpy(buf["o"]))
+        if s is not None:
+            s[i0:i1].copy_(torch.from_numpy(buf["s"]))
+        if e is not None:
+            e[i0:i1].copy_(torch.from_numpy(buf["o_est"]))
+    torch.cuda.synchronize()
+    return o, s, e
+
+
+def cpu_baseline(w, target_seconds):
+    """The oracle as it stands, single-threaded, on the first instances of the workload."""
+    import oracle as O
+    from paper_2601_22996_amd import workloads as W
+    pts = w.sweep()
+    probe = min(4, w.n_instances)
+    d = W.generate(w, 0, min(w.n_instances, 2048))
+    sarg = d["s"] if d["s"] is not None else d["s_scalar"]
+    t = time.perf_counter()
+    r = O.gba_simulate_batch(d["o"], sarg, d["M"], pts, d["o_est"], 0, probe)
+    dt = max(time.perf_counter() - t, 1e-6)
+    cnt = int(max(probe, min(d["o"].shape[0], probe * target_seconds / dt)))
+    t = time.perf_counter()
+    r = O.gba_simulate_batch(d["o"], sarg, d["M"], pts, d["o_est"], 0, cnt)
+    dt = time.perf_counter() - t
+    steps = int(r["job_steps"].sum())
+    return {"value": steps / dt, "unit": "job-decode-steps/s", "cores": 1, "kind": "oracle",
+            "sample": f"instances 0..{cnt - 1} of the workload at all {len(pts)} sweep points, "
+                      f"{steps} job-steps in {dt:.1f} s, literal round-by-round stepping in C (-O2)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the largest sweep)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time of the oracle baseline; 0 skips it")
+    ap.add_argument("--threads", type=int, default=min(16, os.cpu_count() or 1))
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this path runs on ONE GPU (instances are independent; more GPUs would "
+                 "each take a slice of the instance axis). Run with --gpus 1.")
+
+    import torch
+    from paper_2601_22996_amd import kvsched as K
+    from paper_2601_22996_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    K.lib()
+    w = W.WORKLOADS[args.config]
+    pts = w.sweep()
+    o, s, e = load_workload(w, torch, args.threads)
+    sarg = s if s is not None else w.s_scalar
+    out = K.gba_simulate(o, sarg, w.M, pts, o_est=e)          # allocates the outputs once
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        K.gba_simulate(o, sarg, w.M, pts, o_est=e, out=out)
+    torch.cuda.synchronize()
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()                                            # same stream as the kernel
+        K.gba_simulate(o, sarg, w.M, pts, o_est=e, out=out)
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_step = wall * 1e3 / args.steps
+    kern_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    job_steps = int(out["job_steps"].sum().item())
+    feas = out["feasible"]
+    assert int(feas.max().item()) <= 1, "an evaluation reported an in-band error"
+
+    bytes_per_job = 4 * (1 + (s is not None) + (e is not None))
+    n_eval = w.n_instances * len(pts)
+    alg_bytes = n_eval * (w.n_jobs * bytes_per_job + 25)
+    achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
+    res = {
+        "metric": "simulated job-decode-steps/sec on 1 MI355X + % of HBM roofline",
+        "value": job_steps / (ms_step * 1e-3),
+        "unit": "job-decode-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": w.name, "n_instances": w.n_instances, "n_jobs": w.n_jobs,
+                   "M": w.M, "sweep_points": len(pts), "job_steps_per_step": job_steps,
+                   "evaluations_per_step": n_eval},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "kvs_eval_kernel", "kernel_ms": kern_ms,
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "input_bytes_resident": w.n_instances * w.n_jobs * bytes_per_job},
+    }
+    if args.cpu_seconds > 0:
+        res["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,163 @@
+/*
+ * kvsched.h -- C ABI of the MI355X (gfx950) schedule-evaluation library.
+ *
+ * Batched evaluation of the scheduling policies of "Competitive
+ * Non-Clairvoyant KV-Cache Scheduling for LLM Inference" (Feng, Yang, Zhang)
+ * over many independent instances and a sweep of parameters.  Citations name
+ * sections, equations, procedures and algorithms of that paper.
+ *
+ * Model (Section 2.1, "Model and Objective").  An instance is a set of jobs;
+ * job i has a prompt length s_i >= 0 and a response length o_i >= 1 (tokens).
+ * Time runs in rounds t = 0, 1, ...; a job started in round S is active in
+ * the rounds S .. S + d - 1 (d = o_i if it completes, the slice length if it
+ * is killed), occupies s_i + (t - S) + 1 units of KV-cache memory in round t
+ * (eq. (Memory-Feasibility)) and, if it completes, does so at round S + o_i.
+ *   MemPeak  = max over rounds of the summed occupancy of the active jobs;
+ *   feasible = MemPeak <= M;
+ *   FlowTime = sum of the completion rounds.
+ *
+ * Conventions for every entry point
+ *   - plain C, no exceptions; the return value is a status code, 0 = KVS_OK;
+ *   - pointers inside kvs_jobs_t and all output pointers are DEVICE pointers
+ *     (memory of the GPU that is current on the calling thread); the structs
+ *     themselves and the arrays of sweep points are HOST memory, read before
+ *     the call returns;
+ *   - the caller owns every buffer; the library allocates nothing that
+ *     outlives a call and keeps no state between calls;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without waiting; outputs are valid
+ *     once the stream has been synchronised.  kvs_validate is the exception:
+ *     it waits and reports what it found;
+ *   - job arrays are row-major [n_instances][n_jobs], int32;
+ *   - outputs are row-major [n_pts][n_instances].
+ *
+ * Errors that depend on the job data cannot be returned by an asynchronous
+ * call; they are reported in-band, per evaluation, in `feasible`:
+ *   0 / 1                  the schedule exceeds / respects the budget M;
+ *   KVS_FEASIBLE_EINVAL    some job of the instance has o < 1, s < 0,
+ *                          o_est < 1 or s + o > M (per-job feasibility,
+ *                          Section 2.1);
+ *   KVS_FEASIBLE_ERANGE    the evaluation would leave the 32-bit range of the
+ *                          device arithmetic (see "Limits").
+ * In both error cases peak, flow and the remaining outputs of that evaluation
+ * are -1.
+ *
+ * Limits: 1 <= n_jobs <= KVS_MAX_JOBS; lengths (o, s, o_est, tau) at most
+ * 2^30; 1 <= M < 2^40; per phase, n_p * tau_p < 2^31 and
+ * min(n_p, k_p) * (s_max + tau_p + 4096) < 2^31 (n_p jobs take part in the
+ * phase, tau_p is its slice, k_p its parallelism).
+ */
+#ifndef KVSCHED_H
+#define KVSCHED_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVS_OK 0
+#define KVS_EINVAL 1          /* bad argument: null pointer, size or parameter out of range */
+#define KVS_EJOB_INFEASIBLE 2 /* kvs_validate: some job has s + o > M               */
+#define KVS_ERANGE 3          /* kvs_validate: a length exceeds 2^30                */
+#define KVS_EHIP 4            /* a HIP runtime call failed                          */
+#define KVS_ELIMIT 5          /* n_jobs or n_pts above the compiled limits          */
+
+#define KVS_FEASIBLE_EINVAL 0xFE
+#define KVS_FEASIBLE_ERANGE 0xFF
+
+#define KVS_MAX_JOBS 16384 /* jobs per instance (one instance's phase lives in LDS) */
+#define KVS_MAX_POINTS 64  /* sweep points per call                               */
+
+#define KVS_SCHED_SPS 0  /* Staggered-Pipeline-Schedule, Procedure 1               */
+#define KVS_SCHED_SIMS 1 /* Simultaneous-Schedule, appendix "Lower Bounds for SimS" */
+
+#define KVS_MODE_GBA 0 /* Algorithm 2; with o_est: classes by the estimate        */
+#define KVS_MODE_GSA 1 /* Algorithm 1: every unfinished job in every phase        */
+
+/* One batch of instances (Section 2.1: jobs with prompt length s and response
+ * length o; the estimate is what a non-clairvoyant scheduler believes). */
+typedef struct {
+    int32_t n_instances;
+    int32_t n_jobs;
+    const int32_t *o;     /* device, [n_instances][n_jobs], true response lengths >= 1   */
+    const int32_t *s;     /* device, same shape, per-job prompt lengths; NULL: s_scalar  */
+    const int32_t *o_est; /* device, same shape, estimated lengths >= 1; NULL: none      */
+    int32_t s_scalar;     /* common prompt length when s == NULL                         */
+    int64_t M;            /* KV-cache budget in tokens                                   */
+} kvs_jobs_t;
+
+/* One sweep point of kvs_gba_simulate. */
+typedef struct {
+    int32_t tau0;  /* initial slice length tau_0 >= 1; slices are tau_0 * 2^p (Algorithms 1, 2
+                      with scaling factor 2 and a tunable integer initial slice)            */
+    int32_t sched; /* KVS_SCHED_SPS or KVS_SCHED_SIMS: the per-phase subroutine              */
+    int32_t k;     /* 0: per phase the largest memory-feasible parallelism, k*(tau_p, s) of
+                      eq. (max-parallelism) for SPS, floor(M / (s + tau_p)) for SimS, with s
+                      the largest prompt among the phase's jobs, never below 1;
+                      > 0: this parallelism in every phase                                  */
+    int32_t mode;  /* KVS_MODE_GBA or KVS_MODE_GSA                                          */
+} kvs_point_t;
+
+/*
+ * Geometric phases (Algorithm 2 "GBA", Algorithm 1 "GSA") evaluated for every
+ * instance at every sweep point.
+ *
+ * Phase p = 0, 1, ... has the slice tau_p = tau0 * 2^p.  Among the jobs not
+ * yet completed, those the scheduler believes to fit the slice (o_i <= tau_p
+ * in GBA mode without estimates; min(o_est_i, M - s_i) <= tau_p with
+ * estimates; all of them in GSA mode) are run, in input order, by the
+ * subroutine `sched` with slice tau_p: job number r of the phase starts
+ * floor(r * tau_p / k_p) rounds (SPS) or floor(r / k_p) * tau_p rounds (SimS)
+ * after the phase begins, completes after o_i rounds if o_i <= tau_p and is
+ * otherwise killed at the end of its slice and tried again in the next phase.
+ * A phase ends when its last slice ends; a phase without jobs takes no time.
+ *
+ * Outputs (device, [n_pts][n_instances]; job_steps may be NULL):
+ *   peak      MemPeak;  feasible  see above;  flow  FlowTime;
+ *   job_steps number of (job, round) pairs the schedule processes, i.e. the
+ *             simulated decode steps.
+ *
+ * Returns KVS_EINVAL for null required pointers, n_instances < 0, n_jobs < 1,
+ * n_pts < 0, M outside [1, 2^40), s_scalar outside [0, 2^30], tau0 outside
+ * [1, 2^30], k < 0, unknown sched / mode; KVS_ELIMIT above the limits;
+ * KVS_EHIP if the launch fails.  n_instances == 0 or n_pts == 0 is a no-op.
+ */
+int32_t kvs_gba_simulate(const kvs_jobs_t *jobs, const kvs_point_t *pts, int32_t n_pts,
+                         int64_t *peak, uint8_t *feasible, int64_t *flow,
+                         int64_t *job_steps, void *stream);
+
+/*
+ * One invocation of the per-phase subroutine (Procedure 1 for SPS, the
+ * simultaneous schedule for SimS) on the whole job sequence of every
+ * instance, with explicit slice tau[q] and parallelism k[q] (0: automatic as
+ * above) for every point q.  o_est is ignored.  Jobs with o_i <= tau complete
+ * and count towards flow and n_completed; the others are killed when their
+ * slice ends.
+ *
+ * tau, k, sched: host arrays of n_pts entries.  Outputs as above;
+ * n_completed (device, int32, may be NULL) is the number of completed jobs.
+ */
+int32_t kvs_schedule_eval(const kvs_jobs_t *jobs, const int32_t *tau, const int32_t *k,
+                          const int32_t *sched, int32_t n_pts, int64_t *peak,
+                          uint8_t *feasible, int64_t *flow, int32_t *n_completed,
+                          int64_t *job_steps, void *stream);
+
+/*
+ * Scans the job arrays on the device, waits for the result and returns
+ * KVS_OK, KVS_EINVAL (some o < 1, s < 0 or o_est < 1), KVS_ERANGE (a length
+ * above 2^30) or KVS_EJOB_INFEASIBLE (some s + o > M, Section 2.1).  Optional:
+ * the evaluation entry points report the same conditions per instance.
+ */
+int32_t kvs_validate(const kvs_jobs_t *jobs, void *stream);
+
+/* Static, human-readable text for a status code. */
+const char *kvs_strerror(int32_t status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int32_t kvs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVSCHED_H */

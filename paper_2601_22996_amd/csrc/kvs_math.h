@@ -1,0 +1,124 @@
+/*
+ * kvs_math.h -- small integer helpers of the schedule-evaluation kernels.
+ *
+ * Host- and device-callable so that the host tests can drive exactly the
+ * arithmetic the kernels use (class index of the geometric ladder, division
+ * by a per-phase constant, the largest feasible parallelism).
+ *
+ * Citations: "Competitive Non-Clairvoyant KV-Cache Scheduling for LLM
+ * Inference" (Feng, Yang, Zhang).
+ */
+#ifndef KVS_MATH_H
+#define KVS_MATH_H
+
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define KVS_HD __host__ __device__ __forceinline__
+#else
+#define KVS_HD static inline
+#endif
+
+/* Count of leading zero bits; 32 for x == 0. */
+KVS_HD uint32_t kvs_clz32(uint32_t x)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (uint32_t)__clz((int)x);
+#else
+    return x ? (uint32_t)__builtin_clz(x) : 32u;
+#endif
+}
+
+KVS_HD uint32_t kvs_mulhi32(uint32_t a, uint32_t b)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __umulhi(a, b);
+#else
+    return (uint32_t)(((uint64_t)a * (uint64_t)b) >> 32);
+#endif
+}
+
+/* floor(log2 x) for x >= 1. */
+KVS_HD uint32_t kvs_ilog2_floor(uint32_t x) { return 31u - kvs_clz32(x); }
+
+/*
+ * Class of a length x on the ladder tau_p = tau0 * 2^p (Algorithm 2: class p
+ * holds the lengths in (tau_{p-1}, tau_p], class 0 those up to tau_0):
+ * the smallest p >= 0 with tau0 * 2^p >= x.  Needs 1 <= x, tau0 <= 2^30;
+ * lg_tau0 = floor(log2 tau0).
+ *
+ * With g = ceil(log2 x) and m = lg_tau0, 2^m <= tau0 < 2^(m+1) brackets the
+ * answer between g - m - 1 and g - m, so one comparison decides.
+ */
+KVS_HD uint32_t kvs_class_index(uint32_t x, uint32_t tau0, uint32_t lg_tau0)
+{
+    uint32_t g = (x <= 1u) ? 0u : 32u - kvs_clz32(x - 1u);
+    int32_t p1 = (int32_t)g - (int32_t)lg_tau0 - 1;
+    if (p1 < 0)
+        p1 = 0;
+    return ((tau0 << p1) >= x) ? (uint32_t)p1 : (uint32_t)p1 + 1u;
+}
+
+/*
+ * Division of 31-bit dividends by a constant d >= 1 through one multiply-high
+ * and a shift: with l = ceil(log2 d) and mul = floor(2^(31+l) / d) + 1,
+ * floor(x * mul / 2^(31+l)) = floor(x / d) for every 0 <= x < 2^31
+ * (round-up method for N = 31; the error mul*d - 2^(31+l) is at most d <= 2^l).
+ */
+typedef struct {
+    uint32_t mul;   /* 0 encodes d == 1 */
+    uint32_t shift; /* l - 1            */
+} kvs_divisor_t;
+
+KVS_HD kvs_divisor_t kvs_make_divisor(uint32_t d)
+{
+    kvs_divisor_t r;
+    if (d <= 1u) {
+        r.mul = 0u;
+        r.shift = 0u;
+        return r;
+    }
+    uint32_t l = 32u - kvs_clz32(d - 1u); /* ceil(log2 d), >= 1 */
+    r.mul = (uint32_t)((((uint64_t)1) << (31u + l)) / d) + 1u;
+    r.shift = l - 1u;
+    return r;
+}
+
+KVS_HD uint32_t kvs_div(uint32_t x, kvs_divisor_t d)
+{
+    return d.mul ? (kvs_mulhi32(x, d.mul) >> d.shift) : x;
+}
+
+KVS_HD uint64_t kvs_gcd64(uint64_t a, uint64_t b)
+{
+    while (b != 0) {
+        uint64_t r = a % b;
+        a = b;
+        b = r;
+    }
+    return a;
+}
+
+/*
+ * k*(tau, s) = max{k : Peak(k, tau, s) <= M}, eq. (max-parallelism), with
+ * Peak(k, tau, s) = s k + (tau k + tau + k - gcd(tau, k)) / 2 (Lemma "Peak
+ * Memory Usage of SPS").  The proof of Lemma "Feasible Parallelism of SPS"
+ * rewrites the condition as
+ *     k (2s + tau + 1) <= 2M - tau + gcd(tau, k).
+ * As 1 <= gcd <= tau, every feasible k is at most K = floor(2M / (2s+tau+1)),
+ * and K - 1 is feasible whenever it is positive, so only K has to be tested.
+ * Returns 0 if no k >= 1 fits.
+ */
+KVS_HD uint64_t kvs_kstar(uint64_t tau, uint64_t s, uint64_t M)
+{
+    uint64_t den = 2u * s + tau + 1u;
+    uint64_t K = (2u * M) / den;
+    if (K == 0)
+        return 0;
+    /* K * den <= 2M always; compare without forming a negative right side */
+    if (K * den + tau <= 2u * M + kvs_gcd64(tau, K))
+        return K;
+    return K - 1u;
+}
+
+#endif /* KVS_MATH_H */

@@ -1,0 +1,159 @@
+"""Python binding of the C ABI declared in include/kvsched.h.
+
+Argument marshalling only: torch tensors supply device memory and the HIP
+stream; every step of the evaluation runs in the library's kernels.  There is
+no fallback: if the shared library is missing and cannot be built, importing
+a function from here fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+SPS, SIMS = 0, 1
+MODE_GBA, MODE_GSA = 0, 1
+FEASIBLE_EINVAL, FEASIBLE_ERANGE = 0xFE, 0xFF
+OK, EINVAL, EJOB_INFEASIBLE, ERANGE, EHIP, ELIMIT = 0, 1, 2, 3, 4, 5
+MAX_JOBS, MAX_POINTS = 16384, 64
+
+
+class KvsError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"kvsched status {code}: {text}")
+        self.code = code
+
+
+class _Jobs(C.Structure):
+    _fields_ = [("n_instances", C.c_int32), ("n_jobs", C.c_int32),
+                ("o", C.c_void_p), ("s", C.c_void_p), ("o_est", C.c_void_p),
+                ("s_scalar", C.c_int32), ("M", C.c_int64)]
+
+
+class _Point(C.Structure):
+    _fields_ = [("tau0", C.c_int32), ("sched", C.c_int32), ("k", C.c_int32), ("mode", C.c_int32)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def lib():
+    """The loaded shared library; built first only if no built library exists."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build()
+        L = C.CDLL(_build.LIB)
+        vp, i32 = C.c_void_p, C.c_int32
+        L.kvs_gba_simulate.restype = i32
+        L.kvs_gba_simulate.argtypes = [C.POINTER(_Jobs), C.POINTER(_Point), i32, vp, vp, vp, vp, vp]
+        L.kvs_schedule_eval.restype = i32
+        L.kvs_schedule_eval.argtypes = [C.POINTER(_Jobs), C.POINTER(i32), C.POINTER(i32),
+                                        C.POINTER(i32), i32, vp, vp, vp, vp, vp, vp]
+        L.kvs_validate.restype = i32
+        L.kvs_validate.argtypes = [C.POINTER(_Jobs), vp]
+        L.kvs_strerror.restype = C.c_char_p
+        L.kvs_strerror.argtypes = [i32]
+        L.kvs_version.restype = i32
+        L.kvs_host_class_index.restype = C.c_uint32
+        L.kvs_host_class_index.argtypes = [C.c_uint32, C.c_uint32]
+        L.kvs_host_div.restype = C.c_uint32
+        L.kvs_host_div.argtypes = [C.c_uint32, C.c_uint32]
+        L.kvs_host_kstar.restype = C.c_uint64
+        L.kvs_host_kstar.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().kvs_strerror(code).decode()
+
+
+def _check(code: int) -> None:
+    if code != OK:
+        raise KvsError(code, strerror(code))
+
+
+def _dev_i32(t: Optional[torch.Tensor], shape, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous() and tuple(t.shape) == tuple(shape)):
+        raise ValueError(f"{name}: need a contiguous int32 device tensor of shape {tuple(shape)}")
+    return t.data_ptr()
+
+
+def _jobs(o: torch.Tensor, s, M: int, o_est: Optional[torch.Tensor]) -> _Jobs:
+    if o.dim() != 2:
+        raise ValueError("o: need [n_instances][n_jobs]")
+    shape = tuple(o.shape)
+    s_t = s if isinstance(s, torch.Tensor) else None
+    return _Jobs(shape[0], shape[1], _dev_i32(o, shape, "o"), _dev_i32(s_t, shape, "s"),
+                 _dev_i32(o_est, shape, "o_est"), 0 if s_t is not None else int(s), int(M))
+
+
+def _stream(stream) -> Optional[int]:
+    st = torch.cuda.current_stream() if stream is None else stream
+    return st.cuda_stream or None
+
+
+def gba_simulate(o: torch.Tensor, s, M: int, points, o_est: Optional[torch.Tensor] = None,
+                 out: Optional[dict] = None, stream=None) -> dict:
+    """kvs_gba_simulate.  `points`: rows (tau0, sched, k, mode).  `s`: int or
+    device tensor.  Returns device tensors peak, feasible, flow, job_steps of
+    shape [n_pts][n_instances]; valid after the stream is synchronised."""
+    pts = np.asarray(points, dtype=np.int32).reshape(-1, 4)
+    P, I = len(pts), o.shape[0]
+    if out is None:
+        out = dict(peak=torch.empty((P, I), dtype=torch.int64, device=o.device),
+                   feasible=torch.empty((P, I), dtype=torch.uint8, device=o.device),
+                   flow=torch.empty((P, I), dtype=torch.int64, device=o.device),
+                   job_steps=torch.empty((P, I), dtype=torch.int64, device=o.device))
+    arr = (_Point * max(P, 1))(*[_Point(*map(int, r)) for r in pts])
+    jobs = _jobs(o, s, M, o_est)
+    _check(lib().kvs_gba_simulate(C.byref(jobs), arr, P, out["peak"].data_ptr(),
+                                  out["feasible"].data_ptr(), out["flow"].data_ptr(),
+                                  out["job_steps"].data_ptr(), _stream(stream)))
+    return out
+
+
+def schedule_eval(o: torch.Tensor, s, M: int, tau: Sequence[int], k: Sequence[int],
+                  sched: Sequence[int], stream=None) -> dict:
+    """kvs_schedule_eval: one SPS / SimS invocation per point on every instance."""
+    tau = np.ascontiguousarray(tau, dtype=np.int32)
+    k = np.ascontiguousarray(k, dtype=np.int32)
+    sched = np.ascontiguousarray(sched, dtype=np.int32)
+    P, I = len(tau), o.shape[0]
+    if not (len(k) == P and len(sched) == P):
+        raise ValueError("tau, k, sched: need the same length")
+    out = dict(peak=torch.empty((P, I), dtype=torch.int64, device=o.device),
+               feasible=torch.empty((P, I), dtype=torch.uint8, device=o.device),
+               flow=torch.empty((P, I), dtype=torch.int64, device=o.device),
+               n_completed=torch.empty((P, I), dtype=torch.int32, device=o.device),
+               job_steps=torch.empty((P, I), dtype=torch.int64, device=o.device))
+    p32 = C.POINTER(C.c_int32)
+    jobs = _jobs(o, s, M, None)
+    _check(lib().kvs_schedule_eval(C.byref(jobs), tau.ctypes.data_as(p32), k.ctypes.data_as(p32),
+                                   sched.ctypes.data_as(p32), P, out["peak"].data_ptr(),
+                                   out["feasible"].data_ptr(), out["flow"].data_ptr(),
+                                   out["n_completed"].data_ptr(), out["job_steps"].data_ptr(),
+                                   _stream(stream)))
+    return out
+
+
+def validate(o: torch.Tensor, s, M: int, o_est: Optional[torch.Tensor] = None, stream=None) -> int:
+    """kvs_validate: returns the status code (OK, EINVAL, ERANGE, EJOB_INFEASIBLE)."""
+    jobs = _jobs(o, s, M, o_est)
+    return int(lib().kvs_validate(C.byref(jobs), _stream(stream)))
+
+
+def version() -> int:
+    return int(lib().kvs_version())

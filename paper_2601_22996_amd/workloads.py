@@ -14,6 +14,7 @@ range always holds the same numbers whatever else is generated.
 """
 from __future__ import annotations
 
+import threading
 from dataclasses import dataclass, field
 from typing import Optional
 
@@ -63,57 +64,97 @@ WORKLOADS = {
 }
 
 
-def _draw_o(law: str, rng: np.random.Generator, shape) -> np.ndarray:
+_scratch = threading.local()
+
+
+def _buf(shape) -> np.ndarray:
+    """Per-thread float64 scratch, reused between blocks (fresh pages are slow)."""
+    b = getattr(_scratch, "buf", None)
+    if b is None or b.shape != shape:
+        b = np.empty(shape, np.float64)
+        _scratch.buf = b
+    return b
+
+
+def _draw_o(law: str, rng: np.random.Generator, shape, out: np.ndarray) -> None:
+    """Response lengths of one block into `out` (int32), clamped to >= 1."""
     if law == "uniform_1_32":
-        o = rng.integers(1, 33, size=shape)
+        out[...] = rng.integers(1, 33, size=shape)
     elif law == "geometric_256_cap4096":
-        o = np.minimum(rng.geometric(1.0 / 256.0, size=shape), 4096)
+        out[...] = np.minimum(rng.geometric(1.0 / 256.0, size=shape), 4096)
     elif law == "geometric_512_cap8192":
-        o = np.minimum(rng.geometric(1.0 / 512.0, size=shape), 8192)
+        out[...] = np.minimum(rng.geometric(1.0 / 512.0, size=shape), 8192)
     elif law == "lognormal_5_1_cap8192":
-        o = np.clip(np.rint(np.exp(rng.normal(5.0, 1.0, size=shape))), 1, 8192)
+        b = _buf(shape)
+        rng.standard_normal(out=b)
+        np.add(b, 5.0, out=b)                       # N(5, 1)
+        np.exp(b, out=b)
+        np.rint(b, out=b)
+        np.clip(b, 1, 8192, out=b)
+        out[...] = b
     elif law == "pareto_1p5_min16_cap16384":
-        u = 1.0 - rng.random(size=shape)            # in (0, 1]
-        o = np.minimum(np.floor(16.0 * u ** (-1.0 / 1.5)), 16384)
+        b = _buf(shape)
+        rng.random(out=b)
+        np.subtract(1.0, b, out=b)                  # in (0, 1]
+        np.power(b, -1.0 / 1.5, out=b)
+        np.multiply(b, 16.0, out=b)
+        np.floor(b, out=b)
+        np.minimum(b, 16384, out=b)
+        out[...] = b
     else:
         raise ValueError(law)
-    return np.maximum(o, 1).astype(np.int32)
+    np.maximum(out, 1, out=out)
 
 
-def _block(w: Workload, b: int):
+def _block(w: Workload, b: int, o: np.ndarray, s, e) -> None:
+    """Block `b` (BLOCK instances) into the given int32 arrays of shape [BLOCK][n]."""
     rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([w.seed, b])))
     shape = (BLOCK, w.n_jobs)
-    o = _draw_o(w.o_law, rng, shape)
-    s = None
-    if w.s_scalar is None:
+    _draw_o(w.o_law, rng, shape, o)
+    if s is not None:
         lo, hi = w.s_range
-        s = rng.integers(lo, hi + 1, size=shape).astype(np.int32)
-    e = None
-    if w.estimates:
-        noise = np.exp(rng.normal(0.0, 0.5, size=shape))
-        e = np.clip(np.rint(o * noise), 1, w.M - w.s_scalar).astype(np.int32)
-    return o, s, e
+        s[...] = rng.integers(lo, hi + 1, size=shape, dtype=np.int32)
+    if e is not None:
+        f = _buf(shape)
+        rng.standard_normal(out=f)
+        np.multiply(f, 0.5, out=f)                  # N(0, sigma = 0.5)
+        np.exp(f, out=f)
+        np.multiply(f, o, out=f)
+        np.rint(f, out=f)
+        np.clip(f, 1, w.M - w.s_scalar, out=f)
+        e[...] = f
 
 
-def generate(w: Workload, i0: int = 0, i1: Optional[int] = None, threads: int = 1) -> dict:
+def generate(w: Workload, i0: int = 0, i1: Optional[int] = None, threads: int = 1,
+             out: Optional[dict] = None) -> dict:
     """Instances [i0, i1) of workload `w` as row-major int32 arrays.
 
     Returns dict(o=[cnt][n], s=[cnt][n] or None, o_est=[cnt][n] or None,
     s_scalar=int, M=int).  `threads` > 1 draws blocks concurrently; the
-    result does not depend on it."""
+    result does not depend on it.  `out` may hand in arrays of a previous call
+    with the same shapes, to be overwritten."""
     i1 = w.n_instances if i1 is None else i1
     if not (0 <= i0 <= i1 <= w.n_instances):
         raise ValueError("instance range out of bounds")
     cnt = i1 - i0
-    o = np.empty((cnt, w.n_jobs), np.int32)
-    s = np.empty((cnt, w.n_jobs), np.int32) if w.s_scalar is None else None
-    e = np.empty((cnt, w.n_jobs), np.int32) if w.estimates else None
+    if out is not None and out["o"].shape == (cnt, w.n_jobs):
+        o, s, e = out["o"], out["s"], out["o_est"]
+    else:
+        o = np.empty((cnt, w.n_jobs), np.int32)
+        s = np.empty((cnt, w.n_jobs), np.int32) if w.s_scalar is None else None
+        e = np.empty((cnt, w.n_jobs), np.int32) if w.estimates else None
 
     def fill(b: int) -> None:
-        bo, bs, be = _block(w, b)
         lo, hi = max(i0, b * BLOCK), min(i1, (b + 1) * BLOCK)
-        src = slice(lo - b * BLOCK, hi - b * BLOCK)
         dst = slice(lo - i0, hi - i0)
+        if hi - lo == BLOCK:
+            _block(w, b, o[dst], None if s is None else s[dst], None if e is None else e[dst])
+            return
+        bo = np.empty((BLOCK, w.n_jobs), np.int32)
+        bs = np.empty_like(bo) if s is not None else None
+        be = np.empty_like(bo) if e is not None else None
+        _block(w, b, bo, bs, be)
+        src = slice(lo - b * BLOCK, hi - b * BLOCK)
         o[dst] = bo[src]
         if s is not None:
             s[dst] = bs[src]

@@ -449,8 +449,9 @@ def test_error_codes():
 def test_estimate_clamp_reading():
     # An estimate beyond M - s cannot be a real length (per-job feasibility,
     # Section 2.1), so it is clamped to M - s before the class is chosen.
-    # s = 0, M = 12, tau_0 = 3: ladder 3, 6, 12, ...; both jobs claim 100.
+    # s = 4, M = 16, tau_0 = 3: ladder 3, 6, 12, 24, ...; both jobs claim 100.
     # Clamped to 12 they share the phase with slice 12 (k* = 1): completion
-    # rounds 1 and 12 + 1.  Unclamped they would sit in the slice 192.
-    r = O.gba_simulate([1, 1], 0, 12, tau0=3, o_est=[100, 100])
+    # rounds 1 and 12 + 1.  Unclamped they would sit in the slice 192, and
+    # clamped to M instead of M - s in the slice 24.
+    r = O.gba_simulate([1, 1], 4, 16, tau0=3, o_est=[100, 100])
     assert r["flow"] == 1 + 13 and r["n_phases"] == 1 and r["job_steps"] == 2
