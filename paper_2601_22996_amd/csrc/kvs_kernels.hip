@@ -8,29 +8,47 @@
  * Memory Usage of SPS" / "Feasible Parallelism of SPS", Algorithms 1 (GSA)
  * and 2 (GBA).
  *
- * One workgroup evaluates one (instance, sweep point).  No round-by-round
- * stepping happens on the device: inside a phase the occupancy of round t is
+ * Design in one paragraph.  Sweep points whose initial slices are
+ * base * 2^m share one ladder of slices base * 2^g.  One workgroup takes one
+ * instance and one such group of points.  A job's class on the ladder does
+ * not depend on m; a point with shift m merges the levels 0..m into its
+ * first phase and uses the levels above m unchanged.  So every level phase is
+ * evaluated once per (subroutine, parallelism) variant and shared by all the
+ * points, and only the merged first phases are evaluated per shift.  Jobs are
+ * brought into phase order in LDS (a stable multisplit by level when every
+ * job has exactly one phase, stable compaction per phase otherwise).  Inside
+ * a phase nothing is stepped round by round: the occupancy of round t is
  *     occ(t) = A(t) + t * C(t),
  *     C(t) = number of active runs,  A(t) = sum over them of (s + 1 - start),
- * and both are prefix sums over time of per-round event sums (a run adds
+ * both prefix sums over time of per-round event sums (a run adds
  * (s + 1 - start, 1) in its first round and takes it away in the round after
- * its last).  Events are scattered into LDS arrays one time window at a
- * time, scanned by the workgroup, and the maximum of occ is kept.  All values
- * are exact integers, so the result equals the stepped definition.
+ * its last).  The rounds of a phase are cut into slabs; a wavefront takes a
+ * slab, sums the runs already active when it begins, scatters the events
+ * that fall inside into its own LDS window, scans it and keeps the maximum.
+ * Slabs need nothing from each other, so no barrier is taken while phases
+ * are evaluated.  All values are exact integers: the result equals the
+ * stepped definition bit for bit.
  */
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 #include "kvsched.h"
 #include "kvs_math.h"
 
 namespace {
 
-constexpr int kLevels = 32;            /* ladder levels tau0 * 2^p that 2^30-bounded lengths can reach */
-constexpr uint32_t kLenMax = 1u << 30; /* largest length the 32-bit arithmetic is sized for */
+constexpr int kLevels = 32;            /* ladder levels base * 2^g that 2^30-bounded lengths can reach */
+constexpr int kMaxM = 8;               /* distinct shifts m per launch                                  */
+constexpr int kMaxV = 4;               /* distinct (subroutine, parallelism) variants per launch        */
+constexpr int kSlots = kLevels + kMaxM; /* phase slots: one per level, one per merged first phase        */
+constexpr int kWin = 256;              /* rounds in a wavefront's window                                */
+constexpr int kWinPad = kWin + kWin / 32;
+constexpr uint32_t kLenMax = 1u << 30; /* largest length the 32-bit arithmetic is sized for             */
 
 constexpr uint32_t FLAG_EINVAL = 1u;
 constexpr uint32_t FLAG_ERANGE = 2u;
+constexpr uint8_t FEASIBLE_PENDING = 0xFD; /* internal: left for the two-word-entry kernel */
 
 constexpr int MODE_GBA = 0, MODE_GSA = 1, MODE_SINGLE = 2;
 
@@ -44,18 +62,16 @@ struct JobsDev {
     uint64_t M;
 };
 
-struct PointDev {
-    uint32_t tau0;
-    uint32_t k;
-    uint8_t sched;
-    uint8_t mode;
-    uint8_t lg_tau0;
-    uint8_t pad;
-};
-
-struct PointsArg {
-    int32_t n;
-    PointDev p[KVS_MAX_POINTS];
+/* One launch: the points of a sweep that share a ladder. */
+struct GroupArg {
+    uint32_t base;                   /* slice of level 0; level g has base << g                  */
+    uint32_t v_k[kMaxV];             /* forced parallelism per variant, 0 = automatic            */
+    uint16_t pt_q[KVS_MAX_POINTS];   /* output row of each point                                 */
+    uint8_t pt_m[KVS_MAX_POINTS];    /* index into m[]                                           */
+    uint8_t pt_v[KVS_MAX_POINTS];    /* index into the variants                                  */
+    uint8_t m[kMaxM];                /* shifts: the point's initial slice is base << m           */
+    uint8_t v_sched[kMaxV];
+    uint8_t lg_base, mode, n_m, n_v, n_pts;
 };
 
 struct OutsDev {
@@ -66,43 +82,54 @@ struct OutsDev {
     int32_t *n_completed;
 };
 
-/* One phase of one evaluation (a row of the phase table). */
-struct Phase {
-    uint32_t tau; /* slice length tau_p                                  */
-    uint32_t n;   /* participants n_p                                    */
-    uint32_t k;   /* parallelism k_p (SPS) or batch size (SimS), >= 1    */
-    uint32_t H;   /* rounds the phase lasts: last start offset + tau_p   */
-    kvs_divisor_t div;
-    int64_t begin; /* round in which the phase begins                    */
+/* Slot: the jobs of one phase (a level, or the merged first phase of a shift). */
+struct Slot {
+    uint32_t n;     /* participants                                      */
+    uint32_t done;  /* of which complete in this phase                   */
+    uint32_t smax;  /* largest prompt among them                         */
+    uint32_t tau;   /* slice length                                      */
+    uint32_t off;   /* where its entries start in the phase buffer       */
+    uint32_t alias; /* slot whose results it shares, or its own index    */
 };
 
-/* What one job means at one sweep point. */
+/* Variant of a slot: the schedule the subroutine builds on it. */
+struct Sched {
+    uint32_t k; /* parallelism (SPS) or batch size (SimS), >= 1          */
+    uint32_t H; /* rounds the phase lasts                                */
+    uint32_t S; /* slab length used to evaluate it                       */
+    uint32_t nslab;
+    kvs_divisor_t div;
+};
+
+struct Result {
+    int32_t peak;
+    unsigned long long sumF; /* sum of the start offsets of the completing runs */
+};
+
+/* What one job means on the ladder. */
 struct JobView {
     uint32_t o, s;
-    uint32_t enter; /* first phase the job takes part in                 */
-    uint32_t leave; /* last phase it takes part in                       */
-    uint32_t done;  /* class of o: the job completes in phases >= done   */
+    uint32_t ga; /* level at which it first takes part           */
+    uint32_t gb; /* level at which it takes part for the last time */
+    uint32_t go; /* level of o: it completes in phases that reach it */
     bool valid;
 };
 
-__device__ __forceinline__ JobView view_job(const JobsDev &J, size_t idx, const PointDev &pt)
+__device__ __forceinline__ JobView view_job(const JobsDev &J, size_t idx, const GroupArg &G)
 {
     JobView v;
-    int32_t o = J.o[idx];
-    int32_t s = J.s ? J.s[idx] : (int32_t)J.s_scalar;
+    const int32_t o = J.o[idx];
+    const int32_t s = J.s ? J.s[idx] : (int32_t)J.s_scalar;
     v.valid = (o >= 1) && (s >= 0) && ((uint32_t)o <= kLenMax) && ((uint32_t)s <= kLenMax) &&
               ((uint64_t)(uint32_t)s + (uint64_t)(uint32_t)o <= J.M);
     v.o = (o < 1) ? 1u : ((uint32_t)o > kLenMax ? kLenMax : (uint32_t)o);
     v.s = (s < 0) ? 0u : ((uint32_t)s > kLenMax ? kLenMax : (uint32_t)s);
-    v.done = kvs_class_index(v.o, pt.tau0, pt.lg_tau0);
-    if (pt.mode == MODE_SINGLE) {
-        v.enter = 0;
-        v.leave = 0;
-    } else if (pt.mode == MODE_GSA) {
-        v.enter = 0;
-        v.leave = v.done;
+    v.go = kvs_class_index(v.o, G.base, G.lg_base);
+    if (G.mode != MODE_GBA) { /* GSA, or one invocation of the subroutine: everybody from the start */
+        v.ga = 0;
+        v.gb = v.go;
     } else if (J.e) {
-        int32_t e = J.e[idx];
+        const int32_t e = J.e[idx];
         v.valid = v.valid && (e >= 1);
         uint64_t cap = (J.M > v.s) ? (J.M - v.s) : 1u; /* M - s, at least 1 */
         if (cap > kLenMax)
@@ -110,329 +137,615 @@ __device__ __forceinline__ JobView view_job(const JobsDev &J, size_t idx, const 
         uint32_t eu = (e < 1) ? 1u : (uint32_t)e;
         if (eu > (uint32_t)cap)
             eu = (uint32_t)cap;
-        v.enter = kvs_class_index(eu, pt.tau0, pt.lg_tau0);
-        v.leave = v.enter > v.done ? v.enter : v.done;
+        v.ga = kvs_class_index(eu, G.base, G.lg_base);
+        v.gb = v.ga > v.go ? v.ga : v.go;
     } else {
-        v.enter = v.done;
-        v.leave = v.done;
+        v.ga = v.go;
+        v.gb = v.go;
     }
     return v;
 }
 
 /* Start offset of the r-th job of a phase: floor(r tau / k) for SPS
  * (Procedure 1), floor(r / k) tau for SimS. */
-__device__ __forceinline__ uint32_t start_offset(uint32_t r, const Phase &f, bool sps)
+__device__ __forceinline__ uint32_t start_offset(uint32_t r, uint32_t tau, const Sched &c, bool sps)
 {
-    return sps ? kvs_div(r * f.tau, f.div) : kvs_div(r, f.div) * f.tau;
+    return sps ? kvs_div(r * tau, c.div) : kvs_div(r, c.div) * tau;
 }
 
-/* First r in [0, n] with start_offset(r) >= x. */
-__device__ __forceinline__ uint32_t first_rank_at(uint64_t x, const Phase &f, bool sps)
+/* First r in [0, n] whose start offset is >= x.  A floating-point estimate
+ * lands within one of the answer; the exact offsets then decide. */
+__device__ __forceinline__ uint32_t first_rank_at(uint32_t x, uint32_t n, uint32_t tau,
+                                                  const Sched &c, bool sps)
 {
-    uint64_t r;
+    if (x == 0 || n == 0)
+        return 0;
+    double q;
     if (sps)
-        r = (x * f.k + f.tau - 1) / f.tau; /* floor(r tau / k) >= x  <=>  r >= x k / tau */
+        q = ceil((double)x * (double)c.k / (double)tau); /* floor(r tau / k) >= x <=> r >= x k / tau */
     else
-        r = ((x + f.tau - 1) / f.tau) * f.k; /* floor(r / k) >= ceil(x / tau) */
-    return r > f.n ? f.n : (uint32_t)r;
+        q = ceil((double)x / (double)tau) * (double)c.k; /* floor(r / k) >= ceil(x / tau) */
+    uint32_t r = (q >= (double)n) ? n : (uint32_t)q;
+    while (r > 0 && start_offset(r - 1, tau, c, sps) >= x)
+        r--;
+    while (r < n && start_offset(r, tau, c, sps) < x)
+        r++;
+    return r;
+}
+
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
 __device__ __forceinline__ int pad_idx(int i) { return i + (i >> 5); }
 
-template <int T, int TW>
-__global__ __launch_bounds__(T) void kvs_eval_kernel(JobsDev J, PointsArg P, OutsDev out)
+/* How phase entries are laid out in LDS.  One word: prompt | done-bit |
+ * duration, with the field width taken from the instance's largest values;
+ * two words when that does not fit 32 bits. */
+struct EntryFmt {
+    uint32_t dbits; /* duration in bits [0, dbits), done-bit at dbits, prompt above */
+    bool has_s;     /* per-job prompts are stored at all                             */
+};
+
+template <bool PACKED>
+__device__ __forceinline__ void put_entry(uint32_t *buf, uint32_t n_cap, uint32_t pos, uint32_t d,
+                                          bool done, uint32_t s, const EntryFmt &F)
+{
+    if (PACKED) {
+        uint32_t w = d | ((uint32_t)done << F.dbits);
+        if (F.has_s)
+            w |= s << (F.dbits + 1);
+        buf[pos] = w;
+    } else {
+        buf[pos] = d | ((uint32_t)done << 31);
+        buf[n_cap + pos] = s;
+    }
+}
+
+template <bool PACKED>
+__device__ __forceinline__ void get_entry(const uint32_t *buf, uint32_t n_cap, uint32_t pos,
+                                          uint32_t &d, bool &done, uint32_t &s, uint32_t s_scalar,
+                                          const EntryFmt &F)
+{
+    const uint32_t w = buf[pos];
+    if (PACKED) {
+        d = w & ((1u << F.dbits) - 1u);
+        done = (w >> F.dbits) & 1u;
+        s = F.has_s ? (w >> (F.dbits + 1)) : s_scalar;
+    } else {
+        d = w & 0x7fffffffu;
+        done = w >> 31;
+        s = buf[n_cap + pos];
+    }
+}
+
+/*
+ * One slab [t_s, t_s + len) of one phase variant, by one wavefront.
+ * ev: the wavefront's window, kWinPad packed (C << 32) + A event sums.
+ */
+template <bool PACKED>
+__device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool sps, uint32_t slab,
+                                          const uint32_t *buf, uint32_t n_cap, uint32_t s_scalar,
+                                          const EntryFmt &F, unsigned long long *ev, int lane,
+                                          int32_t &pk, unsigned long long &sumF)
+{
+    const uint32_t t_s = slab * sc.S;
+    const uint32_t len = (sc.H - t_s < sc.S) ? (sc.H - t_s) : sc.S;
+    const int per = (int)(sc.S >> 6); /* window entries per lane: 1, 2 or 4 */
+
+    for (int j = 0; j < per; j++)
+        ev[pad_idx(lane * per + j)] = 0ull;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    /* runs that can touch the slab: started after t_s - tau, and before its end */
+    const uint32_t x_lo = (t_s + 1u > sl.tau) ? (t_s + 1u - sl.tau) : 0u;
+    const uint32_t r_lo = first_rank_at(x_lo, sl.n, sl.tau, sc, sps);
+    const uint32_t r_hi = first_rank_at(t_s + len, sl.n, sl.tau, sc, sps);
+
+    int32_t A0 = 0, C0 = 0;
+    bool touched = false;
+    for (uint32_t r = r_lo + lane; r < r_hi; r += 64) {
+        uint32_t d, s;
+        bool done;
+        get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F);
+        const uint32_t f = start_offset(r, sl.tau, sc, sps);
+        const int32_t st = (int32_t)((int64_t)f - (int64_t)t_s); /* in (-tau, len) */
+        const int32_t en = st + (int32_t)d;
+        const int32_t w = (int32_t)s + 1 - st;
+        const unsigned long long evv = (1ull << 32) + (unsigned long long)(long long)w;
+        if (st >= 0) {
+            atomicAdd(&ev[pad_idx(st)], evv);
+            touched = true;
+            if (done)
+                sumF += f;
+        } else if (en > 0) { /* already running when the slab begins */
+            A0 += w;
+            C0 += 1;
+        }
+        if (en > 0 && en < (int32_t)len) {
+            atomicAdd(&ev[pad_idx(en)], 0ull - evv);
+            touched = true;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        A0 += __shfl_xor(A0, off);
+        C0 += __shfl_xor(C0, off);
+    }
+    if (!__any(touched)) {
+        /* nothing starts or ends inside: the occupancy only grows, the last round is the largest */
+        const int32_t occ = A0 + (int32_t)(len - 1u) * C0;
+        pk = occ > pk ? occ : pk;
+        return;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    long long loc[4];
+    long long sum = 0;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        loc[j] = (j < per) ? (long long)ev[pad_idx(lane * per + j)] : 0ll;
+        sum += loc[j];
+    }
+    long long inc = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const long long up = __shfl_up(inc, off);
+        if (lane >= off)
+            inc += up;
+    }
+    long long run = (((long long)C0) << 32) + (long long)A0 + (inc - sum);
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        if (j < per) {
+            run += loc[j];
+            const int32_t A = (int32_t)(uint32_t)run;
+            const int32_t C = (int32_t)((run - (long long)A) >> 32);
+            const int32_t t = lane * per + j;
+            const int32_t occ = A + t * C;
+            if ((uint32_t)t < len && occ > pk)
+                pk = occ;
+        }
+    }
+}
+
+template <int T, bool PACKED>
+__global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, OutsDev out)
 {
     constexpr int NW = T / 64;
-    constexpr int E = TW / T;
-    constexpr int TWP = TW + TW / 32;
-    static_assert(TW % T == 0, "window must be a multiple of the workgroup size");
 
-    extern __shared__ int32_t smem[];
-    int32_t *evA = smem;
-    int32_t *evC = evA + TWP;
-    uint32_t *cd = reinterpret_cast<uint32_t *>(evC + TWP);
-    uint32_t *cs = cd + J.n_jobs;
+    extern __shared__ uint32_t buf[]; /* phase entries: n_jobs words, twice that when !PACKED */
 
-    __shared__ Phase ph[kLevels];
-    __shared__ uint32_t hEnter[kLevels], hLeave[kLevels], sMax[kLevels];
-    __shared__ uint32_t flags;
-    __shared__ uint32_t wtot[2][NW];
-    __shared__ int32_t wsA[NW], wsC[NW];
-    __shared__ int64_t red[4][NW];
+    __shared__ unsigned long long ev[NW][kWinPad];
+    __shared__ uint32_t cumE[NW][kLevels]; /* per wavefront: jobs of its segment entering at levels <= l */
+    __shared__ uint32_t cumL[NW][kLevels]; /* ... leaving at levels <= l                                  */
+    __shared__ uint32_t totE[kLevels], totL[kLevels];
+    __shared__ uint32_t sMaxPart[kLevels], sMaxEnter[kLevels];
+    __shared__ Slot slot[kSlots];
+    __shared__ Sched sched[kMaxV][kSlots];
+    __shared__ Result res[kMaxV][kSlots];
+    __shared__ unsigned long long sumO_sh;
+    __shared__ uint32_t flags, maxO_sh, maxS_sh, maxE_sh;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-
-    /* Workgroups g, g+8, g+16, ... share an XCD (and its L2).  All sweep
-     * points of one instance are put on the same XCD, next to each other in
-     * dispatch order, so the instance's jobs come from HBM once. */
-    const uint32_t g = blockIdx.x;
-    const uint32_t xcd = g & 7u;
-    const uint32_t slot = g >> 3;
-    const uint32_t inst = (slot / (uint32_t)P.n) * 8u + xcd;
-    const uint32_t q = slot % (uint32_t)P.n;
-    if (inst >= (uint32_t)J.n_inst)
-        return;
-
-    const PointDev pt = P.p[q];
-    const bool sps = (pt.sched == KVS_SCHED_SPS);
+    const uint32_t inst = blockIdx.x;
     const uint32_t n = (uint32_t)J.n_jobs;
     const size_t row = (size_t)inst * n;
     const bool per_job_s = (J.s != nullptr);
+    const bool one_phase_each = (G.mode == MODE_GBA) && (J.e == nullptr);
+    const uint32_t m_min = G.m[0];
+
+    if (!PACKED) {
+        /* only the instances the one-word kernel left behind */
+        if (out.feasible[(size_t)G.pt_q[0] * (size_t)J.n_inst + inst] != FEASIBLE_PENDING)
+            return;
+    }
+
+    /* each wavefront owns a contiguous segment of the jobs */
+    const uint32_t seg = ((n + NW - 1) / NW + 63u) & ~63u;
+    const uint32_t seg_lo = (uint32_t)wave * seg < n ? (uint32_t)wave * seg : n;
+    const uint32_t seg_hi = seg_lo + seg < n ? seg_lo + seg : n;
 
     if (tid < kLevels) {
-        hEnter[tid] = 0;
-        hLeave[tid] = 0;
-        sMax[tid] = 0;
+        sMaxPart[tid] = 0;
+        sMaxEnter[tid] = 0;
     }
-    if (tid == 0)
+    if (tid == 0) {
         flags = 0;
-    __syncthreads();
-
-    /* ---- pass 1: how many jobs enter / leave at each level, largest prompt per level ---- */
-    for (uint32_t i = tid; i < n; i += T) {
-        JobView v = view_job(J, row + i, pt);
-        if (!v.valid)
-            atomicOr(&flags, FLAG_EINVAL);
-        atomicAdd(&hEnter[v.enter], 1u);
-        atomicAdd(&hLeave[v.leave], 1u);
-        for (uint32_t l = v.enter; l <= v.leave; l++)
-            atomicMax(&sMax[l], v.s);
+        maxO_sh = 0;
+        maxS_sh = 0;
+        maxE_sh = 0;
+        sumO_sh = 0;
     }
     __syncthreads();
 
-    /* ---- phase table ---- */
-    if (tid < kLevels) {
-        const uint32_t p = tid;
-        uint32_t np = 0;
-        for (uint32_t l = 0; l <= p; l++)
-            np += hEnter[l];
-        for (uint32_t l = 0; l < p; l++)
-            np -= hLeave[l];
-        Phase f;
-        f.n = np;
-        f.tau = 0;
-        f.k = 1;
-        f.H = 0;
-        f.div = kvs_make_divisor(1);
-        f.begin = 0;
-        if (np > 0) {
-            const uint64_t tau = (uint64_t)pt.tau0 << p;
-            const uint64_t smax = sMax[p];
-            if (tau * np >= (1ull << 31)) {
-                atomicOr(&flags, FLAG_ERANGE);
-                f.n = 0;
+    /* ---- pass 1: per wavefront, how many of its jobs enter / leave at each level ---- */
+    {
+        uint32_t cntE = 0, cntL = 0; /* lane l counts level l */
+        unsigned long long sumO = 0;
+        uint32_t mxO = 0, mxS = 0, mxG = 0;
+        bool inval = false;
+        for (uint32_t base = seg_lo; base < seg_hi; base += 64) {
+            const uint32_t i = base + lane;
+            const bool act = i < seg_hi;
+            JobView v;
+            v.ga = v.gb = v.go = 0;
+            v.o = v.s = 0;
+            v.valid = true;
+            if (act) {
+                v = view_job(J, row + i, G);
+                inval |= !v.valid;
+                if (G.mode != MODE_SINGLE || v.go == 0)
+                    sumO += v.o; /* every job completes once; a lone invocation completes o <= tau */
+                mxO = v.o > mxO ? v.o : mxO;
+                mxS = v.s > mxS ? v.s : mxS;
+                mxG = v.gb > mxG ? v.gb : mxG;
+                if (per_job_s) {
+                    atomicMax(&sMaxEnter[v.ga], v.s);
+                    for (uint32_t l = v.ga; l <= v.gb; l++)
+                        atomicMax(&sMaxPart[l], v.s);
+                }
+            }
+            uint64_t todo = __ballot(act);
+            while (todo) {
+                const int src = __ffsll((unsigned long long)todo) - 1;
+                const uint32_t c0 = __builtin_amdgcn_readlane(v.ga, src);
+                const uint64_t mk = __ballot(act && v.ga == c0);
+                if ((uint32_t)lane == c0)
+                    cntE += (uint32_t)__popcll(mk);
+                todo &= ~mk;
+            }
+            if (one_phase_each) {
+                cntL = cntE;
             } else {
-                uint64_t k;
-                if (pt.k > 0)
-                    k = pt.k;
-                else if (sps)
-                    k = kvs_kstar(tau, smax, J.M);
-                else
-                    k = J.M / (smax + tau);
-                if (k < 1)
-                    k = 1;
-                /* beyond these values the start offsets no longer change */
-                const uint64_t kcap = sps ? tau * np : np;
-                if (k > kcap)
-                    k = kcap;
-                const uint64_t act = (k < np) ? k : np;
-                if (act * (smax + tau + TW + 1) >= (1ull << 31))
-                    atomicOr(&flags, FLAG_ERANGE);
-                f.tau = (uint32_t)tau;
-                f.k = (uint32_t)k;
-                f.div = kvs_make_divisor(f.k);
-                f.H = start_offset(np - 1, f, sps) + f.tau;
+                todo = __ballot(act);
+                while (todo) {
+                    const int src = __ffsll((unsigned long long)todo) - 1;
+                    const uint32_t c0 = __builtin_amdgcn_readlane(v.gb, src);
+                    const uint64_t mk = __ballot(act && v.gb == c0);
+                    if ((uint32_t)lane == c0)
+                        cntL += (uint32_t)__popcll(mk);
+                    todo &= ~mk;
+                }
             }
         }
-        ph[p] = f;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int64_t b = 0;
-        for (int p = 0; p < kLevels; p++) {
-            ph[p].begin = b;
-            if (ph[p].n > 0)
-                b += ph[p].H;
+        /* inclusive prefix over levels (lanes 0..31 hold the levels) */
+        uint32_t pe = cntE, pl = cntL;
+#pragma unroll
+        for (int off = 1; off < kLevels; off <<= 1) {
+            const uint32_t ue = __shfl_up(pe, off);
+            const uint32_t ul = __shfl_up(pl, off);
+            if (lane >= off) {
+                pe += ue;
+                pl += ul;
+            }
         }
+        if (lane < kLevels) {
+            cumE[wave][lane] = pe;
+            cumL[wave][lane] = pl;
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            sumO += __shfl_xor(sumO, off);
+            const uint32_t a = __shfl_xor(mxO, off), b = __shfl_xor(mxS, off),
+                           c = __shfl_xor(mxG, off);
+            mxO = a > mxO ? a : mxO;
+            mxS = b > mxS ? b : mxS;
+            mxG = c > mxG ? c : mxG;
+        }
+        if (lane == 0) {
+            atomicAdd(&sumO_sh, sumO);
+            atomicMax(&maxO_sh, mxO);
+            atomicMax(&maxS_sh, mxS);
+            atomicMax(&maxE_sh, mxG);
+        }
+        if (__any(inval) && lane == 0)
+            atomicOr(&flags, FLAG_EINVAL);
     }
     __syncthreads();
 
-    int64_t acc_flow = 0, acc_steps = 0;
-    int32_t acc_done = 0;
-    int32_t pk = 0;
-    uint32_t buf = 0;
+    if (tid < kLevels) {
+        uint32_t e = 0, l = 0;
+        for (int w = 0; w < NW; w++) {
+            e += cumE[w][tid] - (tid ? cumE[w][tid - 1] : 0u);
+            l += cumL[w][tid] - (tid ? cumL[w][tid - 1] : 0u);
+        }
+        totE[tid] = e;
+        totL[tid] = l;
+    }
+    __syncthreads();
+
+    /* ---- entry format: does prompt | done | duration fit one word? ---- */
+    EntryFmt F;
+    {
+        /* durations are at most max(o), or a slice of a level some job reaches */
+        uint64_t dmax = (uint64_t)G.base << maxE_sh;
+        const uint64_t tau_m = (uint64_t)G.base << G.m[G.n_m - 1];
+        if (tau_m > dmax)
+            dmax = tau_m;
+        if (maxO_sh > dmax)
+            dmax = maxO_sh;
+        if (dmax > 0x7fffffffull)
+            dmax = 0x7fffffffull; /* such a phase is out of range anyway */
+        F.dbits = 32u - kvs_clz32((uint32_t)dmax);
+        F.has_s = per_job_s && maxS_sh > 0; /* all-zero prompts need no field */
+        const uint32_t sbits = F.has_s ? 32u - kvs_clz32(maxS_sh) : 0u;
+        const bool fits = F.dbits + 1u + sbits <= 32u;
+        if (PACKED && !fits && flags == 0) {
+            if (tid < G.n_pts)
+                out.feasible[(size_t)G.pt_q[tid] * (size_t)J.n_inst + inst] = FEASIBLE_PENDING;
+            return;
+        }
+        if (!PACKED && fits)
+            return; /* not reachable: the one-word kernel has taken it */
+    }
+
+    /* ---- slots ---- */
+    if (tid < kSlots) {
+        Slot sl;
+        sl.n = 0;
+        sl.done = 0;
+        sl.smax = J.s_scalar;
+        sl.tau = 0;
+        sl.off = 0;
+        sl.alias = (uint32_t)tid;
+        uint32_t lv = 0;
+        bool used = false;
+        if (tid < kLevels) {
+            lv = (uint32_t)tid;
+            used = (G.mode != MODE_SINGLE) && (lv > m_min);
+            if (used) {
+                uint32_t enter = 0, left = 0, off = 0;
+                for (uint32_t l = 0; l <= lv; l++)
+                    enter += totE[l];
+                for (uint32_t l = 0; l < lv; l++)
+                    left += totL[l];
+                sl.n = enter - left;
+                sl.done = totL[lv];
+                if (per_job_s)
+                    sl.smax = sMaxPart[lv];
+                if (one_phase_each) { /* the multisplit keeps every level's jobs side by side */
+                    for (uint32_t l = 0; l < lv; l++)
+                        off += totE[l];
+                    sl.off = off;
+                }
+            }
+        } else if (tid - kLevels < (int)G.n_m) {
+            lv = G.m[tid - kLevels];
+            used = true;
+            uint32_t enter = 0, done = 0, below = 0, sm = 0;
+            for (uint32_t l = 0; l <= lv; l++) {
+                enter += totE[l];
+                done += totL[l];
+                sm = sMaxEnter[l] > sm ? sMaxEnter[l] : sm;
+                if (l < lv)
+                    below += totE[l];
+            }
+            sl.n = enter;
+            sl.done = done;
+            if (per_job_s)
+                sl.smax = sm;
+            /* nobody from below: the merged phase is the level's own phase */
+            if (G.mode != MODE_SINGLE && lv > m_min && below == 0)
+                sl.alias = lv;
+        }
+        if (used && sl.n > 0) {
+            const uint64_t tau = (uint64_t)G.base << lv;
+            if (tau * sl.n >= (1ull << 31)) {
+                atomicOr(&flags, FLAG_ERANGE);
+                sl.n = 0;
+            } else {
+                sl.tau = (uint32_t)tau;
+            }
+        }
+        if (!used)
+            sl.n = 0;
+        slot[tid] = sl;
+    }
+    __syncthreads();
+
+    /* ---- the schedule of every (variant, slot) ---- */
+    for (int i = tid; i < (int)G.n_v * kSlots; i += T) {
+        const int vi = i / kSlots, si = i % kSlots;
+        const Slot sl = slot[si];
+        const bool sps = (G.v_sched[vi] == KVS_SCHED_SPS);
+        Sched sc;
+        sc.k = 1;
+        sc.H = 0;
+        sc.S = 64;
+        sc.nslab = 0;
+        sc.div = kvs_make_divisor(1);
+        if (sl.n > 0) {
+            const uint64_t tau = sl.tau, smax = sl.smax, np = sl.n;
+            uint64_t k;
+            if (G.v_k[vi] > 0)
+                k = G.v_k[vi];
+            else if (sps)
+                k = kvs_kstar(tau, smax, J.M);
+            else
+                k = J.M / (smax + tau);
+            if (k < 1)
+                k = 1;
+            const uint64_t kcap = sps ? tau * np : np; /* beyond this the offsets no longer change */
+            if (k > kcap)
+                k = kcap;
+            const uint64_t act = (k < np) ? k : np;
+            if (act * (smax + tau + kWin + 1) >= (1ull << 31))
+                atomicOr(&flags, FLAG_ERANGE);
+            sc.k = (uint32_t)k;
+            sc.div = kvs_make_divisor(sc.k);
+            sc.H = start_offset(sl.n - 1, sl.tau, sc, sps) + sl.tau;
+            /* slab length: spread the rounds over the wavefronts, 64 to kWin rounds each */
+            uint32_t S = ((sc.H + NW - 1) / NW + 63u) & ~63u;
+            S = S <= 64u ? 64u : (S <= 128u ? 128u : 256u);
+            sc.S = S;
+            sc.nslab = (sc.H + S - 1) / S;
+        }
+        sched[vi][si] = sc;
+        res[vi][si].peak = 0;
+        res[vi][si].sumF = 0;
+    }
+    __syncthreads();
+
     const bool bad = (flags != 0);
+    uint32_t next_item = 0; /* slabs are dealt to the wavefronts in turn */
 
-    for (uint32_t p = 0; p < (uint32_t)kLevels && !bad; p++) {
-        const Phase f = ph[p];
-        if (f.n == 0)
-            continue;
+    auto eval_slot = [&](int si) {
+        const Slot sl = slot[si];
+        if (sl.n == 0 || sl.alias != (uint32_t)si)
+            return;
+        for (int vi = 0; vi < (int)G.n_v; vi++) {
+            const Sched sc = sched[vi][si];
+            const bool sps = (G.v_sched[vi] == KVS_SCHED_SPS);
+            int32_t pk = 0;
+            unsigned long long sumF = 0;
+            bool mine = false;
+            for (uint32_t j = 0; j < sc.nslab; j++) {
+                if ((next_item + j) % NW == (uint32_t)wave) {
+                    eval_slab<PACKED>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk, sumF);
+                    mine = true;
+                }
+            }
+            next_item += sc.nslab;
+            if (mine) {
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    const int32_t op = __shfl_xor(pk, off);
+                    pk = op > pk ? op : pk;
+                    sumF += __shfl_xor(sumF, off);
+                }
+                if (lane == 0) {
+                    atomicMax(&res[vi][si].peak, pk);
+                    atomicAdd(&res[vi][si].sumF, sumF);
+                }
+            }
+        }
+    };
 
-        /* ---- the phase's jobs, in input order, into LDS ---- */
-        uint32_t cnt = 0;
-        for (uint32_t base = 0; base < n; base += T) {
-            const uint32_t i = base + tid;
+    /* stable compaction of the jobs with ga <= lv (<= gb when `level`) into buf[0 ..) */
+    auto compact = [&](uint32_t lv, bool level, uint32_t tau) {
+        uint32_t pos0 = 0;
+        for (int w = 0; w < wave; w++) {
+            uint32_t c = cumE[w][lv];
+            if (level && lv > 0)
+                c -= cumL[w][lv - 1];
+            pos0 += c;
+        }
+        for (uint32_t base = seg_lo; base < seg_hi; base += 64) {
+            const uint32_t i = base + lane;
             bool take = false;
             JobView v;
-            if (i < n) {
-                v = view_job(J, row + i, pt);
-                take = (v.enter <= p) && (p <= v.leave);
+            if (i < seg_hi) {
+                v = view_job(J, row + i, G);
+                take = (v.ga <= lv) && (!level || lv <= v.gb);
             }
             const uint64_t bal = __ballot(take);
-            const uint32_t lrank = __popcll(bal & ((1ull << lane) - 1ull));
-            if (lane == 0)
-                wtot[buf][wave] = (uint32_t)__popcll(bal);
-            __syncthreads();
-            uint32_t wbase = 0, total = 0;
-#pragma unroll
-            for (int w = 0; w < NW; w++) {
-                const uint32_t c = wtot[buf][w];
-                if (w < wave)
-                    wbase += c;
-                total += c;
-            }
             if (take) {
-                const uint32_t r = cnt + wbase + lrank;
-                const bool completes = (v.done <= p);
-                const uint32_t d = completes ? v.o : f.tau;
-                cd[r] = d;
-                if (per_job_s)
-                    cs[r] = v.s;
-                acc_steps += d;
-                if (completes) {
-                    acc_flow += f.begin + (int64_t)start_offset(r, f, sps) + (int64_t)v.o;
-                    acc_done += 1;
-                }
+                const bool done = v.go <= lv;
+                put_entry<PACKED>(buf, n, pos0 + lanes_below(bal), done ? v.o : tau, done, v.s, F);
             }
-            cnt += total;
-            buf ^= 1u;
+            pos0 += (uint32_t)__popcll(bal);
         }
-        __syncthreads();
+    };
 
-        /* ---- occupancy of every round of the phase, one window at a time ---- */
-        int32_t carryA = 0, carryC = 0;
-        for (uint64_t t0 = 0; t0 < f.H; t0 += TW) {
-#pragma unroll
-            for (int j = 0; j < E; j++) {
-                evA[pad_idx(tid + j * T)] = 0;
-                evC[pad_idx(tid + j * T)] = 0;
+    if (!bad) {
+        if (one_phase_each && G.mode != MODE_SINGLE) {
+            /* ---- stable multisplit by level: every level's jobs side by side, input order ---- */
+            uint32_t cur = 0; /* lane l: next free position of level l for this wavefront */
+            if (lane < kLevels) {
+                for (uint32_t l = 0; l < (uint32_t)lane; l++)
+                    cur += totE[l];
+                for (int w = 0; w < wave; w++)
+                    cur += cumE[w][lane] - (lane ? cumE[w][lane - 1] : 0u);
+            }
+            for (uint32_t base = seg_lo; base < seg_hi; base += 64) {
+                const uint32_t i = base + lane;
+                const bool act = i < seg_hi;
+                JobView v;
+                v.ga = 0;
+                if (act)
+                    v = view_job(J, row + i, G);
+                uint32_t pos = 0;
+                uint64_t todo = __ballot(act);
+                while (todo) {
+                    const int src = __ffsll((unsigned long long)todo) - 1;
+                    const uint32_t c0 = __builtin_amdgcn_readlane(v.ga, src);
+                    const uint64_t mk = __ballot(act && v.ga == c0);
+                    const uint32_t b0 = __builtin_amdgcn_readlane(cur, (int)c0);
+                    if (act && v.ga == c0)
+                        pos = b0 + lanes_below(mk);
+                    if ((uint32_t)lane == c0)
+                        cur += (uint32_t)__popcll(mk);
+                    todo &= ~mk;
+                }
+                if (act && v.ga > m_min)
+                    put_entry<PACKED>(buf, n, pos, v.o, true, v.s, F);
             }
             __syncthreads();
-
-            const uint64_t back = (t0 > f.tau) ? (t0 - f.tau) : 0;
-            const uint32_t r_lo = first_rank_at(back, f, sps);
-            const uint32_t r_hi = first_rank_at(t0 + TW, f, sps);
-            for (uint32_t r = r_lo + tid; r < r_hi; r += T) {
-                const int32_t st = (int32_t)((int64_t)start_offset(r, f, sps) - (int64_t)t0);
-                const int32_t d = (int32_t)cd[r];
-                const int32_t s = per_job_s ? (int32_t)cs[r] : (int32_t)J.s_scalar;
-                const int32_t w = s + 1 - st;
-                if ((uint32_t)st < (uint32_t)TW) {
-                    atomicAdd(&evA[pad_idx(st)], w);
-                    atomicAdd(&evC[pad_idx(st)], 1);
-                }
-                const int32_t en = st + d;
-                if ((uint32_t)en < (uint32_t)TW) {
-                    atomicAdd(&evA[pad_idx(en)], -w);
-                    atomicAdd(&evC[pad_idx(en)], -1);
-                }
-            }
+            for (int si = (int)m_min + 1; si < kLevels; si++)
+                eval_slot(si);
             __syncthreads();
-
-            int32_t a[E], c[E];
-            int32_t la = 0, lc = 0;
-#pragma unroll
-            for (int j = 0; j < E; j++) {
-                a[j] = evA[pad_idx(tid * E + j)];
-                c[j] = evC[pad_idx(tid * E + j)];
-                la += a[j];
-                lc += c[j];
+        } else if (G.mode != MODE_SINGLE) {
+            for (int si = (int)m_min + 1; si < kLevels; si++) {
+                if (slot[si].n == 0)
+                    continue;
+                compact((uint32_t)si, true, slot[si].tau);
+                __syncthreads();
+                eval_slot(si);
+                __syncthreads();
             }
-            int32_t va = la, vc = lc;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int32_t ua = __shfl_up(va, off);
-                const int32_t uc = __shfl_up(vc, off);
-                if (lane >= off) {
-                    va += ua;
-                    vc += uc;
-                }
-            }
-            if (lane == 63) {
-                wsA[wave] = va;
-                wsC[wave] = vc;
-            }
+        }
+        /* ---- merged first phases, one per shift ---- */
+        for (int mi = 0; mi < (int)G.n_m; mi++) {
+            const int si = kLevels + mi;
+            if (slot[si].n == 0 || slot[si].alias != (uint32_t)si)
+                continue;
+            compact(G.m[mi], false, slot[si].tau);
             __syncthreads();
-            int32_t ba = 0, bc = 0, ta = 0, tc = 0;
-#pragma unroll
-            for (int w = 0; w < NW; w++) {
-                const int32_t xa = wsA[w], xc = wsC[w];
-                if (w < wave) {
-                    ba += xa;
-                    bc += xc;
-                }
-                ta += xa;
-                tc += xc;
-            }
-            int32_t A = carryA + ba + va - la;
-            int32_t C = carryC + bc + vc - lc;
-            const uint64_t left = f.H - t0; /* rounds of the phase from t0 on */
-#pragma unroll
-            for (int j = 0; j < E; j++) {
-                const int32_t t = tid * E + j;
-                A += a[j];
-                C += c[j];
-                const int32_t occ = A + t * C;
-                if ((uint64_t)t < left && occ > pk)
-                    pk = occ;
-            }
-            /* the next window measures time from t0 + TW */
-            carryC += tc;
-            carryA += ta + TW * carryC;
+            eval_slot(si);
             __syncthreads();
         }
     }
 
-    /* ---- workgroup reduction and store ---- */
-    int64_t r_pk = pk, r_flow = acc_flow, r_steps = acc_steps, r_done = acc_done;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        const int64_t o_pk = __shfl_down(r_pk, off);
-        r_pk = o_pk > r_pk ? o_pk : r_pk;
-        r_flow += __shfl_down(r_flow, off);
-        r_steps += __shfl_down(r_steps, off);
-        r_done += __shfl_down(r_done, off);
-    }
-    if (lane == 0) {
-        red[0][wave] = r_pk;
-        red[1][wave] = r_flow;
-        red[2][wave] = r_steps;
-        red[3][wave] = r_done;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int64_t peak = 0, flow = 0, steps = 0, done = 0;
-        for (int w = 0; w < NW; w++) {
-            peak = red[0][w] > peak ? red[0][w] : peak;
-            flow += red[1][w];
-            steps += red[2][w];
-            done += red[3][w];
+    /* ---- put the phases of every point together ---- */
+    if (tid < G.n_pts) {
+        const int vi = G.pt_v[tid];
+        const int mi = G.pt_m[tid];
+        int64_t begin = 0, flow = (int64_t)sumO_sh, steps = (int64_t)sumO_sh, peak = 0;
+        int64_t done = 0;
+        if (!bad) {
+            int si = kLevels + mi;
+            const int last = (G.mode == MODE_SINGLE) ? 0 : kLevels - 1;
+            for (int g = (int)G.m[mi]; g <= last; g++, si = g) {
+                const Slot sl = slot[si];
+                if (sl.n == 0)
+                    continue;
+                const Result r = res[vi][sl.alias];
+                flow += (int64_t)sl.done * begin + (int64_t)r.sumF;
+                steps += (int64_t)sl.tau * (int64_t)(sl.n - sl.done); /* killed runs use their whole slice */
+                done += sl.done;
+                peak = r.peak > peak ? r.peak : peak;
+                begin += sched[vi][sl.alias].H;
+            }
         }
         uint8_t feas = (peak <= (int64_t)J.M) ? 1 : 0;
-        if (flags & FLAG_EINVAL) {
+        if (flags & FLAG_EINVAL)
             feas = KVS_FEASIBLE_EINVAL;
-        } else if (flags & FLAG_ERANGE) {
+        else if (flags & FLAG_ERANGE)
             feas = KVS_FEASIBLE_ERANGE;
-        }
-        if (flags) {
+        if (bad) {
             peak = -1;
             flow = -1;
             steps = -1;
             done = -1;
         }
-        const size_t oi = (size_t)q * (size_t)J.n_inst + inst;
+        const size_t oi = (size_t)G.pt_q[tid] * (size_t)J.n_inst + inst;
         out.peak[oi] = peak;
         out.feasible[oi] = feas;
         out.flow[oi] = flow;
@@ -445,9 +758,9 @@ __global__ __launch_bounds__(T) void kvs_eval_kernel(JobsDev J, PointsArg P, Out
 
 /* ---- input scan for kvs_validate ---- */
 struct ValidateResult {
-    uint32_t bad_value; /* o < 1, s < 0 or o_est < 1 */
-    uint32_t too_long;  /* a length above 2^30       */
-    uint32_t infeasible; /* s + o > M                */
+    uint32_t bad_value;  /* o < 1, s < 0 or o_est < 1 */
+    uint32_t too_long;   /* a length above 2^30       */
+    uint32_t infeasible; /* s + o > M                 */
 };
 
 __global__ __launch_bounds__(256) void kvs_validate_kernel(JobsDev J, ValidateResult *res)
@@ -508,27 +821,114 @@ JobsDev to_dev(const kvs_jobs_t *jobs, bool use_estimates)
     return J;
 }
 
-template <int T, int TW>
-int32_t launch_eval(const JobsDev &J, const PointsArg &P, const OutsDev &out, hipStream_t st)
+template <int T, bool PACKED>
+int32_t launch_sweep(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
 {
-    constexpr int TWP = TW + TW / 32;
-    const size_t lds = sizeof(int32_t) * (2 * (size_t)TWP + (size_t)J.n_jobs * (J.s ? 2 : 1));
-    auto kern = kvs_eval_kernel<T, TW>;
+    const size_t lds = sizeof(uint32_t) * (size_t)J.n_jobs * (PACKED ? 1 : 2);
+    auto kern = kvs_sweep_kernel<T, PACKED>;
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return KVS_EHIP;
-    const uint64_t groups = ((uint64_t)(J.n_inst + 7) / 8) * 8 * (uint64_t)P.n;
-    if (groups > 0x7fffffffull)
-        return KVS_ELIMIT;
-    hipLaunchKernelGGL(kern, dim3((uint32_t)groups), dim3(T), lds, st, J, P, out);
+    hipLaunchKernelGGL(kern, dim3((uint32_t)J.n_inst), dim3(T), lds, st, J, G, out);
     return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
 }
 
-int32_t run_eval(const JobsDev &J, const PointsArg &P, const OutsDev &out, hipStream_t st)
+int32_t run_group(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
 {
-    if (J.n_jobs <= 2048)
-        return launch_eval<256, 2048>(J, P, out, st);
-    return launch_eval<1024, 4096>(J, P, out, st);
+    int32_t rc;
+    if (J.n_jobs <= 4096)
+        rc = launch_sweep<256, true>(J, G, out, st);
+    else
+        rc = launch_sweep<512, true>(J, G, out, st);
+    if (rc != KVS_OK || !J.s)
+        return rc;
+    /* per-job prompts too wide for one-word entries: second pass over the marked instances */
+    if (J.n_jobs <= 4096)
+        return launch_sweep<256, false>(J, G, out, st);
+    return launch_sweep<512, false>(J, G, out, st);
+}
+
+struct HostPoint {
+    uint32_t tau0, k;
+    int sched, mode, q;
+};
+
+/*
+ * Splits the points into launches.  Points share a launch when their initial
+ * slices are base * 2^m for a common base (the odd part of tau0) and they
+ * have the same mode; a launch holds at most kMaxM shifts and kMaxV variants.
+ * A lone invocation of the subroutine has no ladder: its slice is the base.
+ */
+int32_t run_points(const JobsDev &J, const HostPoint *pts, int n_pts, const OutsDev &out,
+                   hipStream_t st)
+{
+    bool taken[KVS_MAX_POINTS] = {false};
+    for (int first = 0; first < n_pts; first++) {
+        if (taken[first])
+            continue;
+        const int mode = pts[first].mode;
+        const uint32_t base = (mode == MODE_SINGLE)
+                                  ? pts[first].tau0
+                                  : pts[first].tau0 >> __builtin_ctz(pts[first].tau0);
+        GroupArg G;
+        memset(&G, 0, sizeof(G));
+        G.base = base;
+        G.lg_base = (uint8_t)kvs_ilog2_floor(base);
+        G.mode = (uint8_t)mode;
+        for (int i = first; i < n_pts; i++) {
+            if (taken[i] || pts[i].mode != mode)
+                continue;
+            uint32_t m = 0;
+            if (mode == MODE_SINGLE) {
+                if (pts[i].tau0 != base)
+                    continue;
+            } else {
+                m = (uint32_t)__builtin_ctz(pts[i].tau0);
+                if ((pts[i].tau0 >> m) != base)
+                    continue;
+            }
+            int mi = -1, vi = -1;
+            for (int a = 0; a < G.n_m; a++)
+                if (G.m[a] == m)
+                    mi = a;
+            for (int a = 0; a < G.n_v; a++)
+                if (G.v_sched[a] == pts[i].sched && G.v_k[a] == pts[i].k)
+                    vi = a;
+            if ((mi < 0 && G.n_m == kMaxM) || (vi < 0 && G.n_v == kMaxV))
+                continue; /* next launch */
+            if (mi < 0) {
+                mi = G.n_m++;
+                G.m[mi] = (uint8_t)m;
+            }
+            if (vi < 0) {
+                vi = G.n_v++;
+                G.v_sched[vi] = (uint8_t)pts[i].sched;
+                G.v_k[vi] = pts[i].k;
+            }
+            G.pt_m[G.n_pts] = (uint8_t)mi;
+            G.pt_v[G.n_pts] = (uint8_t)vi;
+            G.pt_q[G.n_pts] = (uint16_t)pts[i].q;
+            G.n_pts++;
+            taken[i] = true;
+        }
+        /* the kernel wants the shifts in ascending order */
+        for (int a = 1; a < G.n_m; a++)
+            for (int b = a; b > 0 && G.m[b] < G.m[b - 1]; b--) {
+                const uint8_t t = G.m[b];
+                G.m[b] = G.m[b - 1];
+                G.m[b - 1] = t;
+                for (int p = 0; p < G.n_pts; p++) {
+                    if (G.pt_m[p] == b)
+                        G.pt_m[p] = (uint8_t)(b - 1);
+                    else if (G.pt_m[p] == b - 1)
+                        G.pt_m[p] = (uint8_t)b;
+                }
+            }
+        const int32_t rc = run_group(J, G, out, st);
+        if (rc != KVS_OK)
+            return rc;
+    }
+    return KVS_OK;
 }
 
 } /* namespace */
@@ -550,23 +950,21 @@ int32_t kvs_gba_simulate(const kvs_jobs_t *jobs, const kvs_point_t *pts, int32_t
         return KVS_OK;
     if (!peak || !feasible || !flow)
         return KVS_EINVAL;
-    PointsArg P;
-    P.n = n_pts;
+    HostPoint hp[KVS_MAX_POINTS];
     for (int32_t q = 0; q < n_pts; q++) {
         const kvs_point_t &p = pts[q];
         if (p.tau0 < 1 || (uint32_t)p.tau0 > kLenMax || p.k < 0 ||
             (p.sched != KVS_SCHED_SPS && p.sched != KVS_SCHED_SIMS) ||
             (p.mode != KVS_MODE_GBA && p.mode != KVS_MODE_GSA))
             return KVS_EINVAL;
-        P.p[q].tau0 = (uint32_t)p.tau0;
-        P.p[q].k = (uint32_t)p.k;
-        P.p[q].sched = (uint8_t)p.sched;
-        P.p[q].mode = (uint8_t)(p.mode == KVS_MODE_GSA ? MODE_GSA : MODE_GBA);
-        P.p[q].lg_tau0 = (uint8_t)kvs_ilog2_floor((uint32_t)p.tau0);
-        P.p[q].pad = 0;
+        hp[q].tau0 = (uint32_t)p.tau0;
+        hp[q].k = (uint32_t)p.k;
+        hp[q].sched = p.sched;
+        hp[q].mode = (p.mode == KVS_MODE_GSA) ? MODE_GSA : MODE_GBA;
+        hp[q].q = q;
     }
     OutsDev out{peak, feasible, flow, job_steps, nullptr};
-    return run_eval(to_dev(jobs, true), P, out, static_cast<hipStream_t>(stream));
+    return run_points(to_dev(jobs, true), hp, n_pts, out, static_cast<hipStream_t>(stream));
 }
 
 int32_t kvs_schedule_eval(const kvs_jobs_t *jobs, const int32_t *tau, const int32_t *k,
@@ -584,21 +982,19 @@ int32_t kvs_schedule_eval(const kvs_jobs_t *jobs, const int32_t *tau, const int3
         return KVS_OK;
     if (!peak || !feasible || !flow)
         return KVS_EINVAL;
-    PointsArg P;
-    P.n = n_pts;
+    HostPoint hp[KVS_MAX_POINTS];
     for (int32_t q = 0; q < n_pts; q++) {
         if (tau[q] < 1 || (uint32_t)tau[q] > kLenMax || k[q] < 0 ||
             (sched[q] != KVS_SCHED_SPS && sched[q] != KVS_SCHED_SIMS))
             return KVS_EINVAL;
-        P.p[q].tau0 = (uint32_t)tau[q];
-        P.p[q].k = (uint32_t)k[q];
-        P.p[q].sched = (uint8_t)sched[q];
-        P.p[q].mode = (uint8_t)MODE_SINGLE;
-        P.p[q].lg_tau0 = (uint8_t)kvs_ilog2_floor((uint32_t)tau[q]);
-        P.p[q].pad = 0;
+        hp[q].tau0 = (uint32_t)tau[q];
+        hp[q].k = (uint32_t)k[q];
+        hp[q].sched = sched[q];
+        hp[q].mode = MODE_SINGLE;
+        hp[q].q = q;
     }
     OutsDev out{peak, feasible, flow, job_steps, n_completed};
-    return run_eval(to_dev(jobs, false), P, out, static_cast<hipStream_t>(stream));
+    return run_points(to_dev(jobs, false), hp, n_pts, out, static_cast<hipStream_t>(stream));
 }
 
 int32_t kvs_validate(const kvs_jobs_t *jobs, void *stream)
@@ -656,7 +1052,7 @@ const char *kvs_strerror(int32_t status)
     }
 }
 
-int32_t kvs_version(void) { return 100; }
+int32_t kvs_version(void) { return 200; }
 
 /* Host evaluation of the kernels' integer helpers, for the host-side tests. */
 uint32_t kvs_host_class_index(uint32_t x, uint32_t tau0)
