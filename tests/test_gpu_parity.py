@@ -22,6 +22,7 @@ def K():
     assert torch.cuda.is_available(), "these tests need the GPU"
     from paper_2601_22996_amd import kvsched
     kvsched.lib()
+    assert kvsched.version() >= 200
     return kvsched
 
 
@@ -103,6 +104,54 @@ def test_random_instances_all_modes(K, n, I, hetero, est):
     got = host(K.schedule_eval(dev(o), s if np.isscalar(s) else dev(s), M, tau, k, sc))
     want = O.schedule_eval_batch(o, s, M, list(zip(tau, k, sc)))
     assert_same(got, want, ("peak", "feasible", "flow", "job_steps", "n_completed"))
+
+
+@pytest.mark.parametrize("est,mode", [(False, 0), (True, 0), (False, 1)])
+def test_wide_sweeps_share_one_ladder(K, est, mode):
+    # more shifts and more (subroutine, parallelism) variants than one launch
+    # holds, on three ladders (bases 1, 3, 5), all on the same instances
+    rng = np.random.default_rng(4242 + est + 2 * mode)
+    I, n = 6, 700
+    o = np.minimum(rng.geometric(1.0 / 90, (I, n)), 2000).astype(np.int32)
+    s = rng.integers(0, 300, (I, n)).astype(np.int32)
+    e = np.maximum(1, np.rint(o * np.exp(rng.normal(0, 0.8, o.shape)))).astype(np.int32) if est else None
+    M = 30000
+    pts = [(b << m, sc, k, mode) for b in (1, 3, 5) for m in range(0, 10, 1 if b == 1 else 4)
+           for sc, k in ((0, 0), (1, 0), (0, 9), (1, 9), (0, 40))]
+    for lo in range(0, len(pts), 60):
+        got = run_gba(K, o, s, M, pts[lo:lo + 60], e)
+        want = O.gba_simulate_batch(o, s, M, pts[lo:lo + 60], e)
+        assert_same(got, want)
+
+
+def test_wide_prompts_take_the_two_word_path(K):
+    # prompt and duration together need more than 32 bits in some instances
+    # only: both entry layouts run in the same call
+    rng = np.random.default_rng(99)
+    I, n = 8, 900
+    o = np.minimum(rng.geometric(1.0 / 400, (I, n)), 9000).astype(np.int32)
+    s = rng.integers(0, 2 ** 20, (I, n)).astype(np.int32)
+    s[::2] = s[::2] % 1000                      # even instances stay narrow
+    M = 2 ** 23
+    pts = [(1, 0, 0, 0), (4, 1, 0, 0), (64, 0, 0, 0), (1, 0, 0, 1), (2, 1, 3, 1)]
+    assert_same(run_gba(K, o, s, M, pts), O.gba_simulate_batch(o, s, M, pts))
+    tau, k, sc = [1, 300, 5000, 20000], [0, 2, 0, 5], [0, 1, 1, 0]
+    got = host(K.schedule_eval(dev(o), dev(s), M, tau, k, sc))
+    want = O.schedule_eval_batch(o, s, M, list(zip(tau, k, sc)))
+    assert_same(got, want, ("peak", "feasible", "flow", "job_steps", "n_completed"))
+
+
+def test_largest_instance_size(K):
+    # KVS_MAX_JOBS jobs per instance, one- and two-word entries
+    rng = np.random.default_rng(5)
+    n = K.MAX_JOBS
+    o = np.minimum(rng.geometric(1.0 / 20, (2, n)), 300).astype(np.int32)
+    s = rng.integers(0, 60, (2, n)).astype(np.int32)
+    s[1] = rng.integers(0, 2 ** 24, n)
+    M = 2 ** 26
+    pts = [(1, 0, 0, 0), (8, 1, 0, 0), (2, 0, 0, 1)]
+    assert_same(run_gba(K, o, s, M, pts), O.gba_simulate_batch(o, s, M, pts))
+    assert_same(run_gba(K, o, 7, 5000, pts), O.gba_simulate_batch(o, 7, 5000, pts))
 
 
 def test_long_phases_cross_many_windows(K):
