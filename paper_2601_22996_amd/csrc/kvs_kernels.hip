@@ -313,6 +313,42 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
     }
 }
 
+/*
+ * A phase of at most 64 runs, by one wavefront, one run per lane.  The
+ * occupancy can only fall right after a run's last round, so its maximum is
+ * attained in the last round of some run: every lane evaluates the round in
+ * which its own run ends, summing over all runs of the phase.
+ */
+template <bool PACKED>
+__device__ __forceinline__ void eval_sparse(const Slot &sl, const Sched &sc, bool sps,
+                                            const uint32_t *buf, uint32_t n_cap, uint32_t s_scalar,
+                                            const EntryFmt &F, int lane, int32_t &pk,
+                                            unsigned long long &sumF)
+{
+    uint32_t d = 0, s = 0, f = 0;
+    bool done = false;
+    const bool act = (uint32_t)lane < sl.n;
+    if (act) {
+        get_entry<PACKED>(buf, n_cap, sl.off + (uint32_t)lane, d, done, s, s_scalar, F);
+        f = start_offset((uint32_t)lane, sl.tau, sc, sps);
+        if (done)
+            sumF += f;
+    }
+    const uint32_t s1 = s + 1u;
+    const uint32_t e = f + d;  /* first round after the run */
+    const uint32_t t = e - 1u; /* its last round            */
+    uint32_t occ = 0;
+    for (uint32_t q = 0; q < sl.n; q++) {
+        const uint32_t fq = __builtin_amdgcn_readlane(f, (int)q);
+        const uint32_t eq = __builtin_amdgcn_readlane(e, (int)q);
+        const uint32_t sq = __builtin_amdgcn_readlane(s1, (int)q);
+        if (fq <= t && t < eq)
+            occ += sq + (t - fq);
+    }
+    if (act && (int32_t)occ > pk)
+        pk = (int32_t)occ;
+}
+
 template <int T, bool PACKED>
 __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, OutsDev out)
 {
@@ -606,13 +642,22 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
             int32_t pk = 0;
             unsigned long long sumF = 0;
             bool mine = false;
-            for (uint32_t j = 0; j < sc.nslab; j++) {
-                if ((next_item + j) % NW == (uint32_t)wave) {
-                    eval_slab<PACKED>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk, sumF);
+            if (sl.n <= 64u) {
+                if (next_item % NW == (uint32_t)wave) {
+                    eval_sparse<PACKED>(sl, sc, sps, buf, n, J.s_scalar, F, lane, pk, sumF);
                     mine = true;
                 }
+                next_item += 1;
+            } else {
+                for (uint32_t j = 0; j < sc.nslab; j++) {
+                    if ((next_item + j) % NW == (uint32_t)wave) {
+                        eval_slab<PACKED>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk,
+                                          sumF);
+                        mine = true;
+                    }
+                }
+                next_item += sc.nslab;
             }
-            next_item += sc.nslab;
             if (mine) {
 #pragma unroll
                 for (int off = 32; off > 0; off >>= 1) {
