@@ -42,8 +42,7 @@ constexpr int kLevels = 32;            /* ladder levels base * 2^g that 2^30-bou
 constexpr int kMaxM = 8;               /* distinct shifts m per launch                                  */
 constexpr int kMaxV = 4;               /* distinct (subroutine, parallelism) variants per launch        */
 constexpr int kSlots = kLevels + kMaxM; /* phase slots: one per level, one per merged first phase        */
-constexpr int kWin = 256;              /* rounds in a wavefront's window                                */
-constexpr int kWinPad = kWin + kWin / 32;
+constexpr int kWinMax = 512;           /* most rounds a wavefront's window can hold                     */
 constexpr uint32_t kLenMax = 1u << 30; /* largest length the 32-bit arithmetic is sized for             */
 
 constexpr uint32_t FLAG_EINVAL = 1u;
@@ -90,6 +89,7 @@ struct Slot {
     uint32_t tau;   /* slice length                                      */
     uint32_t off;   /* where its entries start in the phase buffer       */
     uint32_t alias; /* slot whose results it shares, or its own index    */
+    kvs_divisor_t divtau; /* division by tau                             */
 };
 
 /* Variant of a slot: the schedule the subroutine builds on it. */
@@ -153,24 +153,26 @@ __device__ __forceinline__ uint32_t start_offset(uint32_t r, uint32_t tau, const
     return sps ? kvs_div(r * tau, c.div) : kvs_div(r, c.div) * tau;
 }
 
-/* First r in [0, n] whose start offset is >= x.  A floating-point estimate
- * lands within one of the answer; the exact offsets then decide. */
-__device__ __forceinline__ uint32_t first_rank_at(uint32_t x, uint32_t n, uint32_t tau,
-                                                  const Sched &c, bool sps)
+/*
+ * Number of runs of the phase whose start offset is below x, for x <= H.
+ * SPS: floor(r tau / k) < x  <=>  r tau < x k  <=>  r < ceil(x k / tau).
+ * SimS: floor(r / k) tau < x <=>  floor(r / k) < ceil(x / tau).
+ * Past the last start offset the answer is n, which also keeps x * k inside
+ * 31 bits: below it x k <= (n - 1) tau.
+ */
+__device__ __forceinline__ uint32_t ranks_before(uint32_t x, const Slot &sl, const Sched &sc,
+                                                 bool sps)
 {
-    if (x == 0 || n == 0)
+    if (x == 0)
         return 0;
-    double q;
+    if (x > sc.H - sl.tau)
+        return sl.n;
+    uint32_t r;
     if (sps)
-        q = ceil((double)x * (double)c.k / (double)tau); /* floor(r tau / k) >= x <=> r >= x k / tau */
+        r = kvs_div(x * sc.k - 1u, sl.divtau) + 1u;
     else
-        q = ceil((double)x / (double)tau) * (double)c.k; /* floor(r / k) >= ceil(x / tau) */
-    uint32_t r = (q >= (double)n) ? n : (uint32_t)q;
-    while (r > 0 && start_offset(r - 1, tau, c, sps) >= x)
-        r--;
-    while (r < n && start_offset(r, tau, c, sps) < x)
-        r++;
-    return r;
+        r = (kvs_div(x - 1u, sl.divtau) + 1u) * sc.k;
+    return r > sl.n ? sl.n : r;
 }
 
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
@@ -178,8 +180,6 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
                                      __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
-
-__device__ __forceinline__ int pad_idx(int i) { return i + (i >> 5); }
 
 /* How phase entries are laid out in LDS.  One word: prompt | done-bit |
  * duration, with the field width taken from the instance's largest values;
@@ -223,7 +223,8 @@ __device__ __forceinline__ void get_entry(const uint32_t *buf, uint32_t n_cap, u
 
 /*
  * One slab [t_s, t_s + len) of one phase variant, by one wavefront.
- * ev: the wavefront's window, kWinPad packed (C << 32) + A event sums.
+ * ev: the wavefront's window of packed (C << 32) + A event sums, one per round of the slab.
+ * sumF collects the start offsets of the completing runs that start here.
  */
 template <bool PACKED>
 __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool sps, uint32_t slab,
@@ -233,43 +234,52 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
 {
     const uint32_t t_s = slab * sc.S;
     const uint32_t len = (sc.H - t_s < sc.S) ? (sc.H - t_s) : sc.S;
-    const int per = (int)(sc.S >> 6); /* window entries per lane: 1, 2 or 4 */
+    const int per = (int)((len + 63u) >> 6); /* window entries per lane, at most kWinMax / 64 */
 
     for (int j = 0; j < per; j++)
-        ev[pad_idx(lane * per + j)] = 0ull;
+        ev[j * 64 + lane] = 0ull;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
-    /* runs that can touch the slab: started after t_s - tau, and before its end */
-    const uint32_t x_lo = (t_s + 1u > sl.tau) ? (t_s + 1u - sl.tau) : 0u;
-    const uint32_t r_lo = first_rank_at(x_lo, sl.n, sl.tau, sc, sps);
-    const uint32_t r_hi = first_rank_at(t_s + len, sl.n, sl.tau, sc, sps);
+    /* ranks [r0, r1) started less than tau rounds before the slab, [r1, r2) start inside it */
+    const uint32_t r0 = ranks_before((t_s + 1u > sl.tau) ? (t_s + 1u - sl.tau) : 0u, sl, sc, sps);
+    const uint32_t r1 = ranks_before(t_s, sl, sc, sps);
+    const uint32_t r2 = ranks_before(t_s + len, sl, sc, sps);
 
     int32_t A0 = 0, C0 = 0;
-    bool touched = false;
-    for (uint32_t r = r_lo + lane; r < r_hi; r += 64) {
+    bool touched = (r2 > r1);
+    for (uint32_t r = r0 + lane; r < r1; r += 64) {
         uint32_t d, s;
         bool done;
         get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F);
-        const uint32_t f = start_offset(r, sl.tau, sc, sps);
-        const int32_t st = (int32_t)((int64_t)f - (int64_t)t_s); /* in (-tau, len) */
+        const int32_t st = (int32_t)(start_offset(r, sl.tau, sc, sps) - t_s); /* in (-tau, 0) */
         const int32_t en = st + (int32_t)d;
-        const int32_t w = (int32_t)s + 1 - st;
-        const unsigned long long evv = (1ull << 32) + (unsigned long long)(long long)w;
-        if (st >= 0) {
-            atomicAdd(&ev[pad_idx(st)], evv);
-            touched = true;
-            if (done)
-                sumF += f;
-        } else if (en > 0) { /* already running when the slab begins */
+        if (en > 0) { /* still running when the slab begins */
+            const int32_t w = (int32_t)s + 1 - st;
             A0 += w;
             C0 += 1;
-        }
-        if (en > 0 && en < (int32_t)len) {
-            atomicAdd(&ev[pad_idx(en)], 0ull - evv);
-            touched = true;
+            if (en < (int32_t)len) {
+                atomicAdd(&ev[en], 0ull - ((1ull << 32) + (unsigned long long)(long long)w));
+                touched = true;
+            }
         }
     }
+    uint32_t sum_st = 0, n_done = 0; /* per lane: a few runs, offsets below kWin */
+    for (uint32_t r = r1 + lane; r < r2; r += 64) {
+        uint32_t d, s;
+        bool done;
+        get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F);
+        const uint32_t st = start_offset(r, sl.tau, sc, sps) - t_s; /* in [0, len) */
+        const int32_t w = (int32_t)s + 1 - (int32_t)st;
+        const unsigned long long evv = (1ull << 32) + (unsigned long long)(long long)w;
+        atomicAdd(&ev[st], evv);
+        const uint32_t en = st + d;
+        if (en < len)
+            atomicAdd(&ev[en], 0ull - evv);
+        sum_st += done ? st : 0u;
+        n_done += done ? 1u : 0u;
+    }
+    sumF += (unsigned long long)sum_st + (unsigned long long)n_done * (unsigned long long)t_s;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         A0 += __shfl_xor(A0, off);
@@ -284,11 +294,12 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
-    long long loc[4];
+    constexpr int kPer = kWinMax / 64;
+    long long loc[kPer];
     long long sum = 0;
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
-        loc[j] = (j < per) ? (long long)ev[pad_idx(lane * per + j)] : 0ll;
+    for (int j = 0; j < kPer; j++) {
+        loc[j] = (j < per) ? (long long)ev[lane * per + j] : 0ll;
         sum += loc[j];
     }
     long long inc = sum;
@@ -300,7 +311,7 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
     }
     long long run = (((long long)C0) << 32) + (long long)A0 + (inc - sum);
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
+    for (int j = 0; j < kPer; j++) {
         if (j < per) {
             run += loc[j];
             const int32_t A = (int32_t)(uint32_t)run;
@@ -349,14 +360,15 @@ __device__ __forceinline__ void eval_sparse(const Slot &sl, const Sched &sc, boo
         pk = (int32_t)occ;
 }
 
-template <int T, bool PACKED>
+template <int T, bool PACKED, int WIN>
 __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, OutsDev out)
 {
     constexpr int NW = T / 64;
 
     extern __shared__ uint32_t buf[]; /* phase entries: n_jobs words, twice that when !PACKED */
 
-    __shared__ unsigned long long ev[NW][kWinPad];
+    static_assert(WIN % 64 == 0 && WIN <= kWinMax, "window size");
+    __shared__ unsigned long long ev[NW][WIN];
     __shared__ uint32_t cumE[NW][kLevels]; /* per wavefront: jobs of its segment entering at levels <= l */
     __shared__ uint32_t cumL[NW][kLevels]; /* ... leaving at levels <= l                                  */
     __shared__ uint32_t totE[kLevels], totL[kLevels];
@@ -531,6 +543,7 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
         sl.tau = 0;
         sl.off = 0;
         sl.alias = (uint32_t)tid;
+        sl.divtau = kvs_make_divisor(1);
         uint32_t lv = 0;
         bool used = false;
         if (tid < kLevels) {
@@ -578,6 +591,7 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
                 sl.n = 0;
             } else {
                 sl.tau = (uint32_t)tau;
+                sl.divtau = kvs_make_divisor(sl.tau);
             }
         }
         if (!used)
@@ -612,14 +626,19 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
             if (k > kcap)
                 k = kcap;
             const uint64_t act = (k < np) ? k : np;
-            if (act * (smax + tau + kWin + 1) >= (1ull << 31))
+            if (act * (smax + tau + WIN + 1) >= (1ull << 31)) /* window sums stay in 32 bits */
                 atomicOr(&flags, FLAG_ERANGE);
             sc.k = (uint32_t)k;
             sc.div = kvs_make_divisor(sc.k);
             sc.H = start_offset(sl.n - 1, sl.tau, sc, sps) + sl.tau;
-            /* slab length: spread the rounds over the wavefronts, 64 to kWin rounds each */
+            /* slab length: spread the rounds over the wavefronts, 64 to WIN rounds each;
+             * SimS batches do not overlap, so whole batches per slab need no carry-in */
             uint32_t S = ((sc.H + NW - 1) / NW + 63u) & ~63u;
-            S = S <= 64u ? 64u : (S <= 128u ? 128u : 256u);
+            S = S > (uint32_t)WIN ? (uint32_t)WIN : S;
+            if (!sps && sl.tau <= (uint32_t)WIN) {
+                uint32_t b = S / sl.tau;
+                S = sl.tau * (b ? b : 1u);
+            }
             sc.S = S;
             sc.nslab = (sc.H + S - 1) / S;
         }
@@ -866,11 +885,11 @@ JobsDev to_dev(const kvs_jobs_t *jobs, bool use_estimates)
     return J;
 }
 
-template <int T, bool PACKED>
+template <int T, bool PACKED, int WIN>
 int32_t launch_sweep(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
 {
     const size_t lds = sizeof(uint32_t) * (size_t)J.n_jobs * (PACKED ? 1 : 2);
-    auto kern = kvs_sweep_kernel<T, PACKED>;
+    auto kern = kvs_sweep_kernel<T, PACKED, WIN>;
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return KVS_EHIP;
@@ -882,15 +901,15 @@ int32_t run_group(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipSt
 {
     int32_t rc;
     if (J.n_jobs <= 4096)
-        rc = launch_sweep<256, true>(J, G, out, st);
+        rc = launch_sweep<256, true, 384>(J, G, out, st);
     else
-        rc = launch_sweep<512, true>(J, G, out, st);
+        rc = launch_sweep<512, true, 384>(J, G, out, st);
     if (rc != KVS_OK || !J.s)
         return rc;
     /* per-job prompts too wide for one-word entries: second pass over the marked instances */
     if (J.n_jobs <= 4096)
-        return launch_sweep<256, false>(J, G, out, st);
-    return launch_sweep<512, false>(J, G, out, st);
+        return launch_sweep<256, false, 256>(J, G, out, st);
+    return launch_sweep<512, false, 256>(J, G, out, st);
 }
 
 struct HostPoint {
