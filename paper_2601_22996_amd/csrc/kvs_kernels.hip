@@ -264,20 +264,44 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
             }
         }
     }
-    uint32_t sum_st = 0, n_done = 0; /* per lane: a few runs, offsets below kWin */
-    for (uint32_t r = r1 + lane; r < r2; r += 64) {
-        uint32_t d, s;
-        bool done;
-        get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F);
-        const uint32_t st = start_offset(r, sl.tau, sc, sps) - t_s; /* in [0, len) */
-        const int32_t w = (int32_t)s + 1 - (int32_t)st;
-        const unsigned long long evv = (1ull << 32) + (unsigned long long)(long long)w;
-        atomicAdd(&ev[st], evv);
-        const uint32_t en = st + d;
-        if (en < len)
-            atomicAdd(&ev[en], 0ull - evv);
-        sum_st += done ? st : 0u;
-        n_done += done ? 1u : 0u;
+    /* Runs that start inside the slab.  Each lane takes a block of consecutive ranks, so the
+     * runs of one round sit in one lane (two at a block's edge): their start events are summed
+     * in registers and added once, and different lanes work on different rounds -- no lane
+     * fights another for a window entry.  The block length is odd, which spreads the lanes'
+     * LDS reads over all banks. */
+    uint32_t sum_st = 0, n_done = 0; /* per lane: a few runs, offsets below the window size */
+    {
+        const uint32_t blk = ((r2 - r1 + 63u) >> 6) | 1u;
+        const uint32_t rb = r1 + (uint32_t)lane * blk;
+        uint32_t cur = 0, accS = 0, accN = 0;
+        for (uint32_t j = 0; j < blk; j++) {
+            const uint32_t r = rb + j;
+            if (r < r2) {
+                uint32_t d, s;
+                bool done;
+                get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F);
+                const uint32_t st = start_offset(r, sl.tau, sc, sps) - t_s; /* in [0, len) */
+                if (st != cur && accN) {
+                    atomicAdd(&ev[cur], ((unsigned long long)accN << 32) +
+                                            (unsigned long long)(long long)(int32_t)(accS - accN * cur));
+                    accS = 0;
+                    accN = 0;
+                }
+                cur = st;
+                accS += s + 1u;
+                accN += 1u;
+                const uint32_t en = st + d;
+                if (en < len) {
+                    const int32_t w = (int32_t)s + 1 - (int32_t)st;
+                    atomicAdd(&ev[en], 0ull - ((1ull << 32) + (unsigned long long)(long long)w));
+                }
+                sum_st += done ? st : 0u;
+                n_done += done ? 1u : 0u;
+            }
+        }
+        if (accN)
+            atomicAdd(&ev[cur], ((unsigned long long)accN << 32) +
+                                    (unsigned long long)(long long)(int32_t)(accS - accN * cur));
     }
     sumF += (unsigned long long)sum_st + (unsigned long long)n_done * (unsigned long long)t_s;
 #pragma unroll
