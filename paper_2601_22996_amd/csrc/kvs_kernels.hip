@@ -115,11 +115,25 @@ struct JobView {
     bool valid;
 };
 
-__device__ __forceinline__ JobView view_job(const JobsDev &J, size_t idx, const GroupArg &G)
+/* A job as it sits in memory. */
+struct RawJob {
+    int32_t o, s, e;
+};
+
+__device__ __forceinline__ RawJob load_job(const JobsDev &J, size_t idx, bool want_e)
+{
+    RawJob r;
+    r.o = J.o[idx];
+    r.s = J.s ? J.s[idx] : (int32_t)J.s_scalar;
+    r.e = want_e ? J.e[idx] : 1;
+    return r;
+}
+
+__device__ __forceinline__ JobView view_job(const RawJob &r, const JobsDev &J, const GroupArg &G)
 {
     JobView v;
-    const int32_t o = J.o[idx];
-    const int32_t s = J.s ? J.s[idx] : (int32_t)J.s_scalar;
+    const int32_t o = r.o;
+    const int32_t s = r.s;
     v.valid = (o >= 1) && (s >= 0) && ((uint32_t)o <= kLenMax) && ((uint32_t)s <= kLenMax) &&
               ((uint64_t)(uint32_t)s + (uint64_t)(uint32_t)o <= J.M);
     v.o = (o < 1) ? 1u : ((uint32_t)o > kLenMax ? kLenMax : (uint32_t)o);
@@ -129,7 +143,7 @@ __device__ __forceinline__ JobView view_job(const JobsDev &J, size_t idx, const 
         v.ga = 0;
         v.gb = v.go;
     } else if (J.e) {
-        const int32_t e = J.e[idx];
+        const int32_t e = r.e;
         v.valid = v.valid && (e >= 1);
         uint64_t cap = (J.M > v.s) ? (J.M - v.s) : 1u; /* M - s, at least 1 */
         if (cap > kLenMax)
@@ -428,6 +442,10 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
         sMaxPart[tid] = 0;
         sMaxEnter[tid] = 0;
     }
+    for (int i = tid; i < NW * kLevels; i += T) {
+        (&cumE[0][0])[i] = 0;
+        (&cumL[0][0])[i] = 0;
+    }
     if (tid == 0) {
         flags = 0;
         maxO_sh = 0;
@@ -439,54 +457,43 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
 
     /* ---- pass 1: per wavefront, how many of its jobs enter / leave at each level ---- */
     {
-        uint32_t cntE = 0, cntL = 0; /* lane l counts level l */
         unsigned long long sumO = 0;
         uint32_t mxO = 0, mxS = 0, mxG = 0;
         bool inval = false;
+        const bool want_e = (G.mode == MODE_GBA) && (J.e != nullptr);
+        RawJob nxt;
+        nxt.o = nxt.s = nxt.e = 1;
+        if (seg_lo + lane < seg_hi)
+            nxt = load_job(J, row + seg_lo + lane, want_e);
         for (uint32_t base = seg_lo; base < seg_hi; base += 64) {
             const uint32_t i = base + lane;
-            const bool act = i < seg_hi;
-            JobView v;
-            v.ga = v.gb = v.go = 0;
-            v.o = v.s = 0;
-            v.valid = true;
-            if (act) {
-                v = view_job(J, row + i, G);
+            const RawJob raw = nxt;
+            if (i + 64 < seg_hi) /* the next chunk's loads fly while this one is classified */
+                nxt = load_job(J, row + i + 64, want_e);
+            if (i < seg_hi) {
+                const JobView v = view_job(raw, J, G);
                 inval |= !v.valid;
                 if (G.mode != MODE_SINGLE || v.go == 0)
                     sumO += v.o; /* every job completes once; a lone invocation completes o <= tau */
                 mxO = v.o > mxO ? v.o : mxO;
                 mxS = v.s > mxS ? v.s : mxS;
                 mxG = v.gb > mxG ? v.gb : mxG;
-                if (per_job_s) {
-                    atomicMax(&sMaxEnter[v.ga], v.s);
+                atomicAdd(&cumE[wave][v.ga], 1u); /* the wavefront's own histogram */
+                if (!one_phase_each)
+                    atomicAdd(&cumL[wave][v.gb], 1u);
+                if (per_job_s) { /* the maxima settle after a few jobs; then this only reads */
+                    if (v.s > sMaxEnter[v.ga])
+                        atomicMax(&sMaxEnter[v.ga], v.s);
                     for (uint32_t l = v.ga; l <= v.gb; l++)
-                        atomicMax(&sMaxPart[l], v.s);
-                }
-            }
-            uint64_t todo = __ballot(act);
-            while (todo) {
-                const int src = __ffsll((unsigned long long)todo) - 1;
-                const uint32_t c0 = __builtin_amdgcn_readlane(v.ga, src);
-                const uint64_t mk = __ballot(act && v.ga == c0);
-                if ((uint32_t)lane == c0)
-                    cntE += (uint32_t)__popcll(mk);
-                todo &= ~mk;
-            }
-            if (one_phase_each) {
-                cntL = cntE;
-            } else {
-                todo = __ballot(act);
-                while (todo) {
-                    const int src = __ffsll((unsigned long long)todo) - 1;
-                    const uint32_t c0 = __builtin_amdgcn_readlane(v.gb, src);
-                    const uint64_t mk = __ballot(act && v.gb == c0);
-                    if ((uint32_t)lane == c0)
-                        cntL += (uint32_t)__popcll(mk);
-                    todo &= ~mk;
+                        if (v.s > sMaxPart[l])
+                            atomicMax(&sMaxPart[l], v.s);
                 }
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t cntE = (lane < kLevels) ? cumE[wave][lane] : 0u;
+        const uint32_t cntL = one_phase_each ? cntE : ((lane < kLevels) ? cumL[wave][lane] : 0u);
         /* inclusive prefix over levels (lanes 0..31 hold the levels) */
         uint32_t pe = cntE, pl = cntL;
 #pragma unroll
@@ -725,12 +732,20 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
                 c -= cumL[w][lv - 1];
             pos0 += c;
         }
+        const bool want_e = (G.mode == MODE_GBA) && (J.e != nullptr);
+        RawJob nxt;
+        nxt.o = nxt.s = nxt.e = 1;
+        if (seg_lo + lane < seg_hi)
+            nxt = load_job(J, row + seg_lo + lane, want_e);
         for (uint32_t base = seg_lo; base < seg_hi; base += 64) {
             const uint32_t i = base + lane;
             bool take = false;
             JobView v;
+            const RawJob raw = nxt;
+            if (i + 64 < seg_hi)
+                nxt = load_job(J, row + i + 64, want_e);
             if (i < seg_hi) {
-                v = view_job(J, row + i, G);
+                v = view_job(raw, J, G);
                 take = (v.ga <= lv) && (!level || lv <= v.gb);
             }
             const uint64_t bal = __ballot(take);
@@ -752,13 +767,20 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
                 for (int w = 0; w < wave; w++)
                     cur += cumE[w][lane] - (lane ? cumE[w][lane - 1] : 0u);
             }
+            RawJob nxt;
+            nxt.o = nxt.s = nxt.e = 1;
+            if (seg_lo + lane < seg_hi)
+                nxt = load_job(J, row + seg_lo + lane, false);
             for (uint32_t base = seg_lo; base < seg_hi; base += 64) {
                 const uint32_t i = base + lane;
                 const bool act = i < seg_hi;
                 JobView v;
                 v.ga = 0;
+                const RawJob raw = nxt;
+                if (i + 64 < seg_hi)
+                    nxt = load_job(J, row + i + 64, false);
                 if (act)
-                    v = view_job(J, row + i, G);
+                    v = view_job(raw, J, G);
                 uint32_t pos = 0;
                 uint64_t todo = __ballot(act);
                 while (todo) {
