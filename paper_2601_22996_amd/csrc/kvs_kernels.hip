@@ -732,7 +732,12 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
                 c -= cumL[w][lv - 1];
             pos0 += c;
         }
+        /* Pass 1 has vouched for the instance's values, so membership is two comparisons with
+         * slices: entry level <= lv  <=>  believed length <= tau_lv, and so on. */
         const bool want_e = (G.mode == MODE_GBA) && (J.e != nullptr);
+        const uint64_t tl = (uint64_t)G.base << lv;
+        const uint32_t tau_lv = tl > 0xffffffffull ? 0xffffffffu : (uint32_t)tl;
+        const uint32_t tau_below = lv ? (uint32_t)((uint64_t)G.base << (lv - 1)) : 0u;
         RawJob nxt;
         nxt.o = nxt.s = nxt.e = 1;
         if (seg_lo + lane < seg_hi)
@@ -740,18 +745,29 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
         for (uint32_t base = seg_lo; base < seg_hi; base += 64) {
             const uint32_t i = base + lane;
             bool take = false;
-            JobView v;
             const RawJob raw = nxt;
             if (i + 64 < seg_hi)
                 nxt = load_job(J, row + i + 64, want_e);
+            const uint32_t o = (uint32_t)raw.o, s = (uint32_t)raw.s;
             if (i < seg_hi) {
-                v = view_job(raw, J, G);
-                take = (v.ga <= lv) && (!level || lv <= v.gb);
+                uint32_t bel = 1u; /* what the scheduler believes: GSA and lone invocations take everybody */
+                if (G.mode == MODE_GBA) {
+                    bel = o;
+                    if (want_e) {
+                        uint64_t cap = J.M - s;
+                        if (cap > kLenMax)
+                            cap = kLenMax;
+                        bel = (uint32_t)raw.e > (uint32_t)cap ? (uint32_t)cap : (uint32_t)raw.e;
+                    }
+                }
+                take = bel <= tau_lv;
+                if (level && lv > 0)
+                    take = take && ((bel > o ? bel : o) > tau_below);
             }
             const uint64_t bal = __ballot(take);
             if (take) {
-                const bool done = v.go <= lv;
-                put_entry<PACKED>(buf, n, pos0 + lanes_below(bal), done ? v.o : tau, done, v.s, F);
+                const bool done = o <= tau_lv;
+                put_entry<PACKED>(buf, n, pos0 + lanes_below(bal), done ? o : tau, done, s, F);
             }
             pos0 += (uint32_t)__popcll(bal);
         }
@@ -774,13 +790,17 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
             for (uint32_t base = seg_lo; base < seg_hi; base += 64) {
                 const uint32_t i = base + lane;
                 const bool act = i < seg_hi;
-                JobView v;
+                struct {
+                    uint32_t ga, o, s;
+                } v;
                 v.ga = 0;
                 const RawJob raw = nxt;
                 if (i + 64 < seg_hi)
                     nxt = load_job(J, row + i + 64, false);
+                v.o = (uint32_t)raw.o; /* valid: pass 1 has checked the instance */
+                v.s = (uint32_t)raw.s;
                 if (act)
-                    v = view_job(raw, J, G);
+                    v.ga = kvs_class_index(v.o, G.base, G.lg_base);
                 uint32_t pos = 0;
                 uint64_t todo = __ballot(act);
                 while (todo) {
