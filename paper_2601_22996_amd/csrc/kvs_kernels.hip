@@ -287,6 +287,23 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
     {
         const uint32_t blk = ((r2 - r1 + 63u) >> 6) | 1u;
         const uint32_t rb = r1 + (uint32_t)lane * blk;
+        /* inside a block the start offset is carried from rank to rank (quotient and
+         * remainder of r tau / k, or of r / k) instead of divided out each time */
+        uint32_t f = 0, rem = 0;
+        if (rb < r2) {
+            if (sps) {
+                f = kvs_div(rb * sl.tau, sc.div);
+                rem = rb * sl.tau - f * sc.k;
+            } else {
+                const uint32_t b = kvs_div(rb, sc.div);
+                f = b * sl.tau;
+                rem = rb - b * sc.k;
+            }
+        }
+        /* per rank: SPS adds tau to the remainder modulo k, SimS adds 1 modulo k (tau rounds per wrap) */
+        const uint32_t q_step = sps ? kvs_div(sl.tau, sc.div) : 0u;
+        const uint32_t r_step = sps ? sl.tau - q_step * sc.k : 1u;
+        const uint32_t wrap = sps ? 1u : sl.tau;
         uint32_t cur = 0, accS = 0, accN = 0;
         for (uint32_t j = 0; j < blk; j++) {
             const uint32_t r = rb + j;
@@ -294,10 +311,10 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
                 uint32_t d, s;
                 bool done;
                 get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F);
-                const uint32_t st = start_offset(r, sl.tau, sc, sps) - t_s; /* in [0, len) */
+                const uint32_t st = f - t_s; /* in [0, len) */
                 if (st != cur && accN) {
                     atomicAdd(&ev[cur], ((unsigned long long)accN << 32) +
-                                            (unsigned long long)(long long)(int32_t)(accS - accN * cur));
+                                            (unsigned long long)(long long)(int32_t)(accS - __umul24(accN, cur)));
                     accS = 0;
                     accN = 0;
                 }
@@ -311,11 +328,15 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
                 }
                 sum_st += done ? st : 0u;
                 n_done += done ? 1u : 0u;
+                rem += r_step;
+                const bool over = rem >= sc.k;
+                rem -= over ? sc.k : 0u;
+                f += q_step + (over ? wrap : 0u);
             }
         }
         if (accN)
             atomicAdd(&ev[cur], ((unsigned long long)accN << 32) +
-                                    (unsigned long long)(long long)(int32_t)(accS - accN * cur));
+                                    (unsigned long long)(long long)(int32_t)(accS - __umul24(accN, cur)));
     }
     sumF += (unsigned long long)sum_st + (unsigned long long)n_done * (unsigned long long)t_s;
 #pragma unroll
@@ -355,7 +376,7 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
             const int32_t A = (int32_t)(uint32_t)run;
             const int32_t C = (int32_t)((run - (long long)A) >> 32);
             const int32_t t = lane * per + j;
-            const int32_t occ = A + t * C;
+            const int32_t occ = A + __mul24(t, C); /* t < 2^9, |C| < 2^23 by the range check */
             if ((uint32_t)t < len && occ > pk)
                 pk = occ;
         }
