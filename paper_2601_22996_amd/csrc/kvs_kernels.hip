@@ -195,6 +195,60 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
                                      __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
+/*
+ * Wavefront-wide sums and maxima through the VALU's data-parallel lane moves
+ * (DPP), which leave the LDS pipeline to the window atomics.  All 64 lanes
+ * must be active.  Shifts by 1, 2, 4, 8 lanes inside each row of 16 build the
+ * rows' prefixes; the last lane of row 0 / 2 is then broadcast into row
+ * 1 / 3, and lane 31 into rows 2 and 3.
+ */
+template <int CTRL, int ROWS>
+__device__ __forceinline__ int32_t dpp_take(int32_t fill, int32_t v)
+{
+    return __builtin_amdgcn_update_dpp(fill, v, CTRL, ROWS, 0xf, false);
+}
+
+/* inclusive prefix sum over the lanes */
+__device__ __forceinline__ int32_t wave_prefix_add(int32_t v)
+{
+    v += dpp_take<0x111, 0xf>(0, v); /* row_shr:1 */
+    v += dpp_take<0x112, 0xf>(0, v); /* row_shr:2 */
+    v += dpp_take<0x114, 0xf>(0, v); /* row_shr:4 */
+    v += dpp_take<0x118, 0xf>(0, v); /* row_shr:8 */
+    v += dpp_take<0x142, 0xa>(0, v); /* row_bcast:15 into rows 1 and 3 */
+    v += dpp_take<0x143, 0xc>(0, v); /* row_bcast:31 into rows 2 and 3 */
+    return v;
+}
+
+/* sum over the lanes, the same value in every lane */
+__device__ __forceinline__ int32_t wave_sum(int32_t v)
+{
+    return __builtin_amdgcn_readlane(wave_prefix_add(v), 63);
+}
+
+/* maximum over the lanes of values >= 0, the same value in every lane */
+__device__ __forceinline__ int32_t wave_max_nonneg(int32_t v)
+{
+    int32_t u;
+    u = dpp_take<0x111, 0xf>(0, v); v = u > v ? u : v;
+    u = dpp_take<0x112, 0xf>(0, v); v = u > v ? u : v;
+    u = dpp_take<0x114, 0xf>(0, v); v = u > v ? u : v;
+    u = dpp_take<0x118, 0xf>(0, v); v = u > v ? u : v;
+    u = dpp_take<0x142, 0xa>(0, v); v = u > v ? u : v;
+    u = dpp_take<0x143, 0xc>(0, v); v = u > v ? u : v;
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
+/* sum over the lanes of 63-bit values, in three limbs of 21 bits */
+__device__ __forceinline__ unsigned long long wave_sum_u63(unsigned long long v)
+{
+    const uint32_t m = (1u << 21) - 1u;
+    const unsigned long long a = (uint32_t)wave_sum((int32_t)((uint32_t)v & m));
+    const unsigned long long b = (uint32_t)wave_sum((int32_t)((uint32_t)(v >> 21) & m));
+    const unsigned long long c = (uint32_t)wave_sum((int32_t)((uint32_t)(v >> 42) & m));
+    return a + (b << 21) + (c << 42);
+}
+
 /* How phase entries are laid out in LDS.  One word: prompt | done-bit |
  * duration, with the field width taken from the instance's largest values;
  * two words when that does not fit 32 bits. */
@@ -339,11 +393,8 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
                                     (unsigned long long)(long long)(int32_t)(accS - __umul24(accN, cur)));
     }
     sumF += (unsigned long long)sum_st + (unsigned long long)n_done * (unsigned long long)t_s;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        A0 += __shfl_xor(A0, off);
-        C0 += __shfl_xor(C0, off);
-    }
+    A0 = wave_sum(A0);
+    C0 = wave_sum(C0);
     if (!__any(touched)) {
         /* nothing starts or ends inside: the occupancy only grows, the last round is the largest */
         const int32_t occ = A0 + (int32_t)(len - 1u) * C0;
@@ -354,27 +405,23 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
     __builtin_amdgcn_wave_barrier();
 
     constexpr int kPer = kWinMax / 64;
-    long long loc[kPer];
-    long long sum = 0;
+    int32_t la[kPer], lc[kPer];
+    int32_t sa = 0, sc_ = 0;
 #pragma unroll
     for (int j = 0; j < kPer; j++) {
-        loc[j] = (j < per) ? (long long)ev[lane * per + j] : 0ll;
-        sum += loc[j];
+        const unsigned long long e = (j < per) ? ev[lane * per + j] : 0ull;
+        la[j] = (int32_t)(uint32_t)e;                        /* A, signed low word          */
+        lc[j] = (int32_t)(uint32_t)(e >> 32) - (la[j] >> 31); /* C: undo the low word's borrow */
+        sa += la[j];
+        sc_ += lc[j];
     }
-    long long inc = sum;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const long long up = __shfl_up(inc, off);
-        if (lane >= off)
-            inc += up;
-    }
-    long long run = (((long long)C0) << 32) + (long long)A0 + (inc - sum);
+    int32_t A = A0 + wave_prefix_add(sa) - sa;
+    int32_t C = C0 + wave_prefix_add(sc_) - sc_;
 #pragma unroll
     for (int j = 0; j < kPer; j++) {
         if (j < per) {
-            run += loc[j];
-            const int32_t A = (int32_t)(uint32_t)run;
-            const int32_t C = (int32_t)((run - (long long)A) >> 32);
+            A += la[j];
+            C += lc[j];
             const int32_t t = lane * per + j;
             const int32_t occ = A + __mul24(t, C); /* t < 2^9, |C| < 2^23 by the range check */
             if ((uint32_t)t < len && occ > pk)
@@ -730,12 +777,8 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
                 next_item += sc.nslab;
             }
             if (mine) {
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) {
-                    const int32_t op = __shfl_xor(pk, off);
-                    pk = op > pk ? op : pk;
-                    sumF += __shfl_xor(sumF, off);
-                }
+                pk = wave_max_nonneg(pk);
+                sumF = wave_sum_u63(sumF);
                 if (lane == 0) {
                     atomicMax(&res[vi][si].peak, pk);
                     atomicAdd(&res[vi][si].sumF, sumF);
