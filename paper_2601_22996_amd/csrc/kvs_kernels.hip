@@ -730,9 +730,10 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
             sc.k = (uint32_t)k;
             sc.div = kvs_make_divisor(sc.k);
             sc.H = start_offset(sl.n - 1, sl.tau, sc, sps) + sl.tau;
-            /* slab length: spread the rounds over the wavefronts, 64 to WIN rounds each;
+            /* slab length: about two wavefronts' share of the rounds, 64 to WIN rounds each (longer
+             * slabs repeat less work at their edges, and that outweighs the balance);
              * SimS batches do not overlap, so whole batches per slab need no carry-in */
-            uint32_t S = ((sc.H + NW - 1) / NW + 63u) & ~63u;
+            uint32_t S = ((2 * sc.H + NW - 1) / NW + 63u) & ~63u;
             S = S > (uint32_t)WIN ? (uint32_t)WIN : S;
             if (!sps && sl.tau <= (uint32_t)WIN) {
                 uint32_t b = S / sl.tau;
@@ -1030,10 +1031,12 @@ int32_t launch_sweep(const JobsDev &J, const GroupArg &G, const OutsDev &out, hi
 int32_t run_group(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
 {
     int32_t rc;
+    /* Large instances: 12 wavefronts and 256-round windows keep two workgroups (24 wavefronts)
+     * on a compute unit next to a 40 KB phase buffer; measured best among the shapes tried. */
     if (J.n_jobs <= 4096)
         rc = launch_sweep<256, true, 384>(J, G, out, st);
     else
-        rc = launch_sweep<512, true, 384>(J, G, out, st);
+        rc = launch_sweep<768, true, 256>(J, G, out, st);
     if (rc != KVS_OK || !J.s)
         return rc;
     /* per-job prompts too wide for one-word entries: second pass over the marked instances */
