@@ -25,6 +25,31 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 CHUNK = 4096                   # instances generated and uploaded at a time
+TRAFFIC_NOTE = os.path.join(ROOT, "profiles", "kvs_sweep_kernel_cfg5_pareto_traffic.md")
+
+
+def kernel_source_digest():
+    """sha256 over the sources the evaluation kernel is built from."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in ("paper_2601_22996_amd/csrc/kvs_kernels.hip", "paper_2601_22996_amd/csrc/kvs_math.h"):
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload_name):
+    """HBM bytes per launch from the committed rocprofv3 --pmc note, or None when the note is
+    for another workload or the kernel sources have changed since it was taken."""
+    try:
+        text = open(TRAFFIC_NOTE).read()
+    except OSError:
+        return None
+    kv = dict(line.strip("- ").split(": ", 1) for line in text.splitlines()
+              if line.startswith("- ") and ": " in line)
+    if kv.get("workload") != workload_name or kv.get("source_sha256") != kernel_source_digest():
+        return None
+    return int(kv["traffic_bytes_per_launch"])
 
 
 def load_workload(w, torch, threads):
@@ -77,6 +102,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the largest sweep)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time of the oracle baseline; 0 skips it")
     ap.add_argument("--threads", type=int, default=min(16, os.cpu_count() or 1))
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run three plain 1 GiB device-to-device copies: a kernel of known traffic "
+                         "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this path runs on ONE GPU (instances are independent; more GPUs would "
@@ -96,6 +124,14 @@ def main():
     sarg = s if s is not None else w.s_scalar
     out = K.gba_simulate(o, sarg, w.M, pts, o_est=e)          # allocates the outputs once
     torch.cuda.synchronize()
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.int32, device="cuda:0").random_(0, 1000)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         K.gba_simulate(o, sarg, w.M, pts, o_est=e, out=out)
@@ -134,7 +170,7 @@ def main():
                    "M": w.M, "sweep_points": len(pts), "job_steps_per_step": job_steps,
                    "evaluations_per_step": n_eval},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "kernel": "kvs_sweep_kernel", "kernel_ms": kern_ms,
                      "algorithmic_bytes_per_launch": alg_bytes,
                      # the fused kernel reads an instance once per launch, not once per point
