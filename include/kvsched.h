@@ -44,8 +44,8 @@
  *
  * Limits: 1 <= n_jobs <= KVS_MAX_JOBS; lengths (o, s, o_est, tau) at most
  * 2^30; 1 <= M < 2^40; per phase, n_p * tau_p < 2^31 and
- * min(n_p, k_p) * (s_max + tau_p + 4096) < 2^31 (n_p jobs take part in the
- * phase, tau_p is its slice, k_p its parallelism).
+ * min(n_p, k_p) * (s_max + tau_p + 513) < 2^31 (n_p jobs take part in the
+ * phase, tau_p is its slice, k_p its parallelism, s_max its largest prompt).
  */
 #ifndef KVSCHED_H
 #define KVSCHED_H
@@ -68,6 +68,7 @@ extern "C" {
 
 #define KVS_MAX_JOBS 16384 /* jobs per instance (one instance's phase lives in LDS) */
 #define KVS_MAX_POINTS 64  /* sweep points per call                               */
+#define KVS_MAX_LEVELS 64  /* slices of an explicit ladder                        */
 
 #define KVS_SCHED_SPS 0  /* Staggered-Pipeline-Schedule, Procedure 1               */
 #define KVS_SCHED_SIMS 1 /* Simultaneous-Schedule, appendix "Lower Bounds for SimS" */
@@ -142,6 +143,37 @@ int32_t kvs_schedule_eval(const kvs_jobs_t *jobs, const int32_t *tau, const int3
                           const int32_t *sched, int32_t n_pts, int64_t *peak,
                           uint8_t *feasible, int64_t *flow, int32_t *n_completed,
                           int64_t *job_steps, void *stream);
+
+/*
+ * kvs_gba_simulate on explicit ladders of slice lengths: any scaling factor
+ * alpha and initial slice of Algorithms 1 and 2, whose phases use the integer
+ * slices tau_p = floor(beta alpha^p).  Point q runs its phases p = 0, 1, ...
+ * with the slices ladders[q * KVS_MAX_LEVELS + p], p < n_levels[q]; a job's
+ * class is the first slice that covers its (believed) length.  sched, k, mode
+ * as in kvs_point_t.  Everything else as kvs_gba_simulate.
+ *
+ * ladders: host, int32 [n_pts][KVS_MAX_LEVELS], each row non-decreasing with
+ * entries in [1, 2^30] (else KVS_EINVAL); n_levels, sched, k, mode: host,
+ * n_pts entries.  An instance with a length above the last slice of a ladder
+ * has no class there and is reported in-band as KVS_FEASIBLE_EINVAL.
+ */
+int32_t kvs_ladder_simulate(const kvs_jobs_t *jobs, const int32_t *ladders,
+                            const int32_t *n_levels, const int32_t *sched, const int32_t *k,
+                            const int32_t *mode, int32_t n_pts, int64_t *peak, uint8_t *feasible,
+                            int64_t *flow, int64_t *job_steps, void *stream);
+
+/*
+ * The ladder Algorithms 1 and 2 initialise for a common prompt length s and a
+ * rational scaling factor alpha = alpha_num / alpha_den > 1:
+ *   l = floor(log_alpha(M - s)),  beta = (M - s) / alpha^l  (so 1 <= beta < alpha),
+ *   tau_p = floor(beta alpha^p),  p = 0 .. l,  tau_l = M - s,
+ * in exact integer arithmetic.  Host only.  ladder: room for KVS_MAX_LEVELS
+ * entries; *n_levels receives l + 1.  KVS_EINVAL for M <= s, s < 0,
+ * M - s > 2^30 or alpha <= 1; KVS_ELIMIT if the ladder needs more than
+ * KVS_MAX_LEVELS levels or the exact arithmetic would leave 128 bits.
+ */
+int32_t kvs_paper_ladder(int64_t M, int64_t s, int32_t alpha_num, int32_t alpha_den,
+                         int32_t *ladder, int32_t *n_levels);
 
 /*
  * Scans the job arrays on the device, waits for the result and returns

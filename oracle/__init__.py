@@ -71,6 +71,14 @@ def lib():
         _lib.kvo_gba_simulate_batch.restype = C.c_int
         _lib.kvo_gba_simulate_batch.argtypes = [i64, i64, i64, p32, p32, p32, i64, i64, i64,
                                                 p32, p32, p32, p32, p64, pu8, p64, p64]
+        _lib.kvo_ladder_simulate.restype = C.c_int
+        _lib.kvo_ladder_simulate.argtypes = [i64, p32, p32, p32, i64, i64, p32, i64, C.c_int, i64,
+                                             C.c_int, p64, p32, p64, p64, p64]
+        _lib.kvo_ladder_simulate_batch.restype = C.c_int
+        _lib.kvo_ladder_simulate_batch.argtypes = [i64, i64, i64, p32, p32, p32, i64, i64, i64,
+                                                   p32, i64, p32, p32, p32, p32, p64, pu8, p64, p64]
+        _lib.kvo_paper_ladder.restype = i64
+        _lib.kvo_paper_ladder.argtypes = [i64, i64, i64, i64, p32, i64]
         _lib.kvo_schedule_eval_batch.restype = C.c_int
         _lib.kvo_schedule_eval_batch.argtypes = [i64, i64, i64, p32, p32, i64, i64, i64,
                                                  p32, p32, p32, p64, pu8, p64, p32, p64]
@@ -148,6 +156,62 @@ def gba_simulate(o, s, M, tau0=1, sched=SPS, k=0, mode=MODE_GBA, o_est=None):
                                   C.byref(steps), C.byref(phases)))
     return dict(peak=peak.value, feasible=feas.value, flow=flow.value,
                 job_steps=steps.value, n_phases=phases.value)
+
+
+def paper_ladder(M: int, s: int, num: int, den: int = 1, max_levels: int = 128):
+    """Slices floor(beta alpha^p), p = 0..l, of Algorithms 1 and 2 for alpha = num/den."""
+    lad = np.zeros(max_levels, np.int32)
+    L = lib().kvo_paper_ladder(M, s, num, den, _p32(lad), max_levels)
+    if L < 0:
+        raise OracleError(EINVAL)
+    return lad[:L].copy()
+
+
+def ladder_simulate(o, s, M, ladder, sched=SPS, k=0, mode=MODE_GBA, o_est=None):
+    """One instance on an explicit ladder of slices.  `s`: int or array."""
+    o = _i32(o)
+    s_arr = None if np.isscalar(s) else _i32(s)
+    s_scalar = int(s) if np.isscalar(s) else 0
+    e = _i32(o_est)
+    lad = _i32(ladder)
+    peak, flow, steps, phases = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
+    feas = C.c_int32()
+    _check(lib().kvo_ladder_simulate(len(o), _p32(o), _p32(s_arr), _p32(e), s_scalar, M,
+                                     _p32(lad), len(lad), sched, k, mode, C.byref(peak),
+                                     C.byref(feas), C.byref(flow), C.byref(steps),
+                                     C.byref(phases)))
+    return dict(peak=peak.value, feasible=feas.value, flow=flow.value,
+                job_steps=steps.value, n_phases=phases.value)
+
+
+def ladder_simulate_batch(o, s, M, ladders, points, o_est=None, i0=0, i1=None):
+    """Instances [i0, i1) at every point q = (sched, k, mode) on the slices ladders[q]
+    (a list of 1-d arrays).  Returns dict of arrays shaped [n_pts][i1 - i0]."""
+    o = _i32(o)
+    I, n = o.shape
+    i1 = I if i1 is None else i1
+    s_arr = None if np.isscalar(s) else _i32(s)
+    s_scalar = int(s) if np.isscalar(s) else 0
+    e = _i32(o_est)
+    pts = np.asarray(points, dtype=np.int32).reshape(-1, 3)
+    sched, k, mode = (np.ascontiguousarray(pts[:, j]) for j in range(3))
+    P, cnt = len(pts), i1 - i0
+    stride = max(len(l) for l in ladders)
+    lad = np.zeros((P, stride), np.int32)
+    nlv = np.zeros(P, np.int32)
+    for q, l in enumerate(ladders):
+        lad[q, :len(l)] = l
+        nlv[q] = len(l)
+    peak = np.zeros((P, cnt), np.int64)
+    flow = np.zeros((P, cnt), np.int64)
+    steps = np.zeros((P, cnt), np.int64)
+    feas = np.zeros((P, cnt), np.uint8)
+    _check(lib().kvo_ladder_simulate_batch(i0, i1, n, _p32(o), _p32(s_arr), _p32(e), s_scalar,
+                                           M, P, _p32(lad), stride, _p32(nlv), _p32(sched),
+                                           _p32(k), _p32(mode), _p64(peak),
+                                           feas.ctypes.data_as(C.POINTER(C.c_uint8)), _p64(flow),
+                                           _p64(steps)))
+    return dict(peak=peak, feasible=feas, flow=flow, job_steps=steps)
 
 
 def gba_simulate_batch(o, s, M, points, o_est=None, i0=0, i1=None):

@@ -297,11 +297,12 @@ int kvo_schedule_eval(int64_t n, const int32_t *o, const int32_t *s,
  * All runs of all phases are then stepped round by round for the occupancy
  * peak; the flow time is the sum of the completion rounds.
  */
-int kvo_gba_simulate(int64_t n, const int32_t *o, const int32_t *s,
-                     const int32_t *o_est, int64_t s_scalar, int64_t M,
-                     int64_t tau0, int sched, int64_t k, int mode,
-                     int64_t *peak, int32_t *feasible, int64_t *flow,
-                     int64_t *job_steps, int64_t *n_phases_used)
+static int phase_driver(int64_t n, const int32_t *o, const int32_t *s,
+                        const int32_t *o_est, int64_t s_scalar, int64_t M,
+                        int64_t tau0, const int32_t *ladder, int64_t n_levels,
+                        int sched, int64_t k, int mode,
+                        int64_t *peak, int32_t *feasible, int64_t *flow,
+                        int64_t *job_steps, int64_t *n_phases_used)
 {
     kvo_run_t *runs = NULL;
     int64_t cap = 0, nr = 0;
@@ -349,11 +350,19 @@ int kvo_gba_simulate(int64_t n, const int32_t *o, const int32_t *s,
     rc = KVO_OK;
     for (p = 0; left > 0; p++) {
         int64_t tau, nJ = 0, s_max = 0, kk, r;
-        if (p > 40) { /* tau_0 * 2^40 exceeds any int32 length */
-            rc = KVO_EINVAL;
-            break;
+        if (ladder) {
+            if (p >= n_levels) { /* a job that no slice of the ladder covers */
+                rc = KVO_EINVAL;
+                break;
+            }
+            tau = ladder[p];
+        } else {
+            if (p > 40) { /* tau_0 * 2^40 exceeds any int32 length */
+                rc = KVO_EINVAL;
+                break;
+            }
+            tau = tau0 << p;
         }
-        tau = tau0 << p;
         for (i = 0; i < n; i++)
             if (in_T[i] && e[i] <= tau)
                 J[nJ++] = i;
@@ -409,6 +418,75 @@ int kvo_gba_simulate(int64_t n, const int32_t *o, const int32_t *s,
     return KVO_OK;
 }
 
+/* Slices tau_p = tau_0 * 2^p (scaling factor 2, integer initial slice). */
+int kvo_gba_simulate(int64_t n, const int32_t *o, const int32_t *s,
+                     const int32_t *o_est, int64_t s_scalar, int64_t M,
+                     int64_t tau0, int sched, int64_t k, int mode,
+                     int64_t *peak, int32_t *feasible, int64_t *flow,
+                     int64_t *job_steps, int64_t *n_phases_used)
+{
+    return phase_driver(n, o, s, o_est, s_scalar, M, tau0, NULL, 0, sched, k,
+                        mode, peak, feasible, flow, job_steps, n_phases_used);
+}
+
+/* Slices given one by one: ladder[0] <= ladder[1] <= ... (n_levels of them),
+ * e.g. tau_p = floor(beta alpha^p) for any scaling factor alpha. */
+int kvo_ladder_simulate(int64_t n, const int32_t *o, const int32_t *s,
+                        const int32_t *o_est, int64_t s_scalar, int64_t M,
+                        const int32_t *ladder, int64_t n_levels, int sched,
+                        int64_t k, int mode, int64_t *peak, int32_t *feasible,
+                        int64_t *flow, int64_t *job_steps,
+                        int64_t *n_phases_used)
+{
+    int64_t p;
+    if (!ladder || n_levels < 1 || ladder[0] < 1)
+        return KVO_EINVAL;
+    for (p = 1; p < n_levels; p++)
+        if (ladder[p] < ladder[p - 1])
+            return KVO_EINVAL;
+    return phase_driver(n, o, s, o_est, s_scalar, M, 1, ladder, n_levels, sched,
+                        k, mode, peak, feasible, flow, job_steps,
+                        n_phases_used);
+}
+
+/*
+ * The initialisation of Algorithms 1 and 2 for a rational scaling factor
+ * alpha = num / den > 1 and a common prompt length s:
+ *   l = floor(log_alpha(M - s)), beta = (M - s) / alpha^l,
+ *   tau_p = floor(beta alpha^p) for p = 0 .. l.
+ * Exact: beta alpha^p = (M - s) * (den/num)^(l-p), and the powers are kept as
+ * 128-bit integers.  Returns the number of levels l + 1, or -1 when more than
+ * max_levels are needed or a power leaves the 128-bit range.
+ */
+int64_t kvo_paper_ladder(int64_t M, int64_t s, int64_t num, int64_t den,
+                         int32_t *ladder, int64_t max_levels)
+{
+    unsigned __int128 span, top = ((unsigned __int128)1) << 126;
+    unsigned __int128 pow_num[130], pow_den[130];
+    int64_t l, p;
+    if (M <= s || s < 0 || den < 1 || num <= den)
+        return -1;
+    span = (unsigned __int128)(M - s);
+    pow_num[0] = 1;
+    pow_den[0] = 1;
+    /* largest l with alpha^l <= M - s, i.e. num^l <= (M - s) den^l */
+    for (l = 0;; l++) {
+        /* the next powers, and (M - s) times the power of den, must stay below 2^126 */
+        if (l + 1 >= 129 || pow_num[l] > top / (unsigned __int128)num ||
+            pow_den[l] > top / ((unsigned __int128)den * span))
+            return -1;
+        pow_num[l + 1] = pow_num[l] * (unsigned __int128)num;
+        pow_den[l + 1] = pow_den[l] * (unsigned __int128)den;
+        if (pow_num[l + 1] > span * pow_den[l + 1])
+            break;
+    }
+    if (l + 1 > max_levels)
+        return -1;
+    for (p = 0; p <= l; p++)
+        ladder[p] = (int32_t)((span * pow_den[l - p]) / pow_num[l - p]);
+    return l + 1;
+}
+
 /* Batch form used by the parity tests and the CPU-baseline timing: instances
  * [i0, i1) of row-major [n_instances][n] arrays at every sweep point; outputs
  * are [n_pts][i1 - i0].  Stops at the first error. */
@@ -431,6 +509,34 @@ int kvo_gba_simulate_batch(int64_t i0, int64_t i1, int64_t n,
                                       M, tau0[q], sched[q], k[q], mode[q],
                                       &peak[idx], &feas, &flow[idx],
                                       &job_steps[idx], NULL);
+            if (rc != KVO_OK)
+                return rc;
+            feasible[idx] = (uint8_t)feas;
+        }
+    return KVO_OK;
+}
+
+/* Same for explicit ladders: ladders is [n_pts][stride]. */
+int kvo_ladder_simulate_batch(int64_t i0, int64_t i1, int64_t n,
+                              const int32_t *o, const int32_t *s,
+                              const int32_t *o_est, int64_t s_scalar, int64_t M,
+                              int64_t n_pts, const int32_t *ladders,
+                              int64_t stride, const int32_t *n_levels,
+                              const int32_t *sched, const int32_t *k,
+                              const int32_t *mode, int64_t *peak,
+                              uint8_t *feasible, int64_t *flow,
+                              int64_t *job_steps)
+{
+    int64_t q, i, cnt = i1 - i0;
+    for (q = 0; q < n_pts; q++)
+        for (i = i0; i < i1; i++) {
+            int32_t feas = 0;
+            int64_t idx = q * cnt + (i - i0);
+            int rc = kvo_ladder_simulate(n, o + i * n, s ? s + i * n : NULL,
+                                         o_est ? o_est + i * n : NULL, s_scalar,
+                                         M, ladders + q * stride, n_levels[q],
+                                         sched[q], k[q], mode[q], &peak[idx],
+                                         &feas, &flow[idx], &job_steps[idx], NULL);
             if (rc != KVO_OK)
                 return rc;
             feasible[idx] = (uint8_t)feas;

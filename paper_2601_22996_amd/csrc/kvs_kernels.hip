@@ -38,10 +38,10 @@
 
 namespace {
 
-constexpr int kLevels = 32;            /* ladder levels base * 2^g that 2^30-bounded lengths can reach */
+constexpr int kLevelsGeo = 32;         /* ladder levels base * 2^g that 2^30-bounded lengths can reach */
+constexpr int kLevelsMax = KVS_MAX_LEVELS; /* levels of an explicit ladder                              */
 constexpr int kMaxM = 8;               /* distinct shifts m per launch                                  */
 constexpr int kMaxV = 4;               /* distinct (subroutine, parallelism) variants per launch        */
-constexpr int kSlots = kLevels + kMaxM; /* phase slots: one per level, one per merged first phase        */
 constexpr int kWinMax = 512;           /* most rounds a wavefront's window can hold                     */
 constexpr uint32_t kLenMax = 1u << 30; /* largest length the 32-bit arithmetic is sized for             */
 
@@ -71,6 +71,8 @@ struct GroupArg {
     uint8_t m[kMaxM];                /* shifts: the point's initial slice is base << m           */
     uint8_t v_sched[kMaxV];
     uint8_t lg_base, mode, n_m, n_v, n_pts;
+    uint8_t n_lv;                    /* > 0: the slices are ladder[0 .. n_lv), not base << g     */
+    uint32_t ladder[kLevelsMax];
 };
 
 struct OutsDev {
@@ -129,7 +131,31 @@ __device__ __forceinline__ RawJob load_job(const JobsDev &J, size_t idx, bool wa
     return r;
 }
 
-__device__ __forceinline__ JobView view_job(const RawJob &r, const JobsDev &J, const GroupArg &G)
+/* Level of a length on the launch's ladder: the smallest g whose slice is >= x.
+ * Geometric ladders (base << g) answer with a leading-zero count; explicit
+ * ones are searched (lad holds the n_lv slices in LDS, non-decreasing); a
+ * length above the last slice has no level and is reported through ok. */
+template <bool EXPLICIT>
+__device__ __forceinline__ uint32_t level_of(uint32_t x, const GroupArg &G, const uint32_t *lad,
+                                             bool &ok)
+{
+    if (!EXPLICIT)
+        return kvs_class_index(x, G.base, G.lg_base);
+    uint32_t p = 0; /* number of slices below x */
+#pragma unroll
+    for (uint32_t b = kLevelsMax / 2; b > 0; b >>= 1)
+        if (p + b - 1u < G.n_lv && lad[p + b - 1u] < x)
+            p += b;
+    if (p >= G.n_lv) {
+        ok = false;
+        p = G.n_lv - 1u;
+    }
+    return p;
+}
+
+template <bool EXPLICIT>
+__device__ __forceinline__ JobView view_job(const RawJob &r, const JobsDev &J, const GroupArg &G,
+                                            const uint32_t *lad)
 {
     JobView v;
     const int32_t o = r.o;
@@ -138,7 +164,7 @@ __device__ __forceinline__ JobView view_job(const RawJob &r, const JobsDev &J, c
               ((uint64_t)(uint32_t)s + (uint64_t)(uint32_t)o <= J.M);
     v.o = (o < 1) ? 1u : ((uint32_t)o > kLenMax ? kLenMax : (uint32_t)o);
     v.s = (s < 0) ? 0u : ((uint32_t)s > kLenMax ? kLenMax : (uint32_t)s);
-    v.go = kvs_class_index(v.o, G.base, G.lg_base);
+    v.go = level_of<EXPLICIT>(v.o, G, lad, v.valid);
     if (G.mode != MODE_GBA) { /* GSA, or one invocation of the subroutine: everybody from the start */
         v.ga = 0;
         v.gb = v.go;
@@ -151,7 +177,7 @@ __device__ __forceinline__ JobView view_job(const RawJob &r, const JobsDev &J, c
         uint32_t eu = (e < 1) ? 1u : (uint32_t)e;
         if (eu > (uint32_t)cap)
             eu = (uint32_t)cap;
-        v.ga = kvs_class_index(eu, G.base, G.lg_base);
+        v.ga = level_of<EXPLICIT>(eu, G, lad, v.valid);
         v.gb = v.ga > v.go ? v.ga : v.go;
     } else {
         v.ga = v.go;
@@ -466,10 +492,14 @@ __device__ __forceinline__ void eval_sparse(const Slot &sl, const Sched &sc, boo
         pk = (int32_t)occ;
 }
 
-template <int T, bool PACKED, int WIN>
+template <int T, bool PACKED, int WIN, int LV>
 __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, OutsDev out)
 {
     constexpr int NW = T / 64;
+    constexpr int kLevels = LV;          /* levels of the ladder this instantiation can hold */
+    constexpr int kSlots = LV + kMaxM;   /* phase slots: one per level, one per merged first phase */
+    constexpr bool EXPLICIT = (LV == kLevelsMax); /* explicit ladders get the large instantiation */
+    static_assert(LV == kLevelsGeo || LV == kLevelsMax, "levels");
 
     extern __shared__ uint32_t buf[]; /* phase entries: n_jobs words, twice that when !PACKED */
 
@@ -479,6 +509,7 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
     __shared__ uint32_t cumL[NW][kLevels]; /* ... leaving at levels <= l                                  */
     __shared__ uint32_t totE[kLevels], totL[kLevels];
     __shared__ uint32_t sMaxPart[kLevels], sMaxEnter[kLevels];
+    __shared__ uint32_t lad[kLevels]; /* slice of every level, saturated at 2^32 - 1 */
     __shared__ Slot slot[kSlots];
     __shared__ Sched sched[kMaxV][kSlots];
     __shared__ Result res[kMaxV][kSlots];
@@ -509,6 +540,12 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
     if (tid < kLevels) {
         sMaxPart[tid] = 0;
         sMaxEnter[tid] = 0;
+        if (EXPLICIT) {
+            lad[tid] = (tid < (int)G.n_lv) ? G.ladder[tid] : 0xffffffffu;
+        } else {
+            const uint64_t tl = (uint64_t)G.base << tid;
+            lad[tid] = tl > 0xffffffffull ? 0xffffffffu : (uint32_t)tl;
+        }
     }
     for (int i = tid; i < NW * kLevels; i += T) {
         (&cumE[0][0])[i] = 0;
@@ -539,7 +576,7 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
             if (i + 64 < seg_hi) /* the next chunk's loads fly while this one is classified */
                 nxt = load_job(J, row + i + 64, want_e);
             if (i < seg_hi) {
-                const JobView v = view_job(raw, J, G);
+                const JobView v = view_job<EXPLICIT>(raw, J, G, lad);
                 inval |= !v.valid;
                 if (G.mode != MODE_SINGLE || v.go == 0)
                     sumO += v.o; /* every job completes once; a lone invocation completes o <= tau */
@@ -612,8 +649,8 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
     EntryFmt F;
     {
         /* durations are at most max(o), or a slice of a level some job reaches */
-        uint64_t dmax = (uint64_t)G.base << maxE_sh;
-        const uint64_t tau_m = (uint64_t)G.base << G.m[G.n_m - 1];
+        uint64_t dmax = lad[maxE_sh];
+        const uint64_t tau_m = lad[G.m[G.n_m - 1]];
         if (tau_m > dmax)
             dmax = tau_m;
         if (maxO_sh > dmax)
@@ -684,7 +721,7 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
                 sl.alias = lv;
         }
         if (used && sl.n > 0) {
-            const uint64_t tau = (uint64_t)G.base << lv;
+            const uint64_t tau = lad[lv];
             if (tau * sl.n >= (1ull << 31)) {
                 atomicOr(&flags, FLAG_ERANGE);
                 sl.n = 0;
@@ -800,9 +837,8 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
         /* Pass 1 has vouched for the instance's values, so membership is two comparisons with
          * slices: entry level <= lv  <=>  believed length <= tau_lv, and so on. */
         const bool want_e = (G.mode == MODE_GBA) && (J.e != nullptr);
-        const uint64_t tl = (uint64_t)G.base << lv;
-        const uint32_t tau_lv = tl > 0xffffffffull ? 0xffffffffu : (uint32_t)tl;
-        const uint32_t tau_below = lv ? (uint32_t)((uint64_t)G.base << (lv - 1)) : 0u;
+        const uint32_t tau_lv = lad[lv];
+        const uint32_t tau_below = lv ? lad[lv - 1] : 0u;
         RawJob nxt;
         nxt.o = nxt.s = nxt.e = 1;
         if (seg_lo + lane < seg_hi)
@@ -864,8 +900,10 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
                     nxt = load_job(J, row + i + 64, false);
                 v.o = (uint32_t)raw.o; /* valid: pass 1 has checked the instance */
                 v.s = (uint32_t)raw.s;
-                if (act)
-                    v.ga = kvs_class_index(v.o, G.base, G.lg_base);
+                if (act) {
+                    bool ok = true; /* checked in pass 1 */
+                    v.ga = level_of<EXPLICIT>(v.o, G, lad, ok);
+                }
                 uint32_t pos = 0;
                 uint64_t todo = __ballot(act);
                 while (todo) {
@@ -1016,11 +1054,11 @@ JobsDev to_dev(const kvs_jobs_t *jobs, bool use_estimates)
     return J;
 }
 
-template <int T, bool PACKED, int WIN>
+template <int T, bool PACKED, int WIN, int LV>
 int32_t launch_sweep(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
 {
     const size_t lds = sizeof(uint32_t) * (size_t)J.n_jobs * (PACKED ? 1 : 2);
-    auto kern = kvs_sweep_kernel<T, PACKED, WIN>;
+    auto kern = kvs_sweep_kernel<T, PACKED, WIN, LV>;
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return KVS_EHIP;
@@ -1031,23 +1069,31 @@ int32_t launch_sweep(const JobsDev &J, const GroupArg &G, const OutsDev &out, hi
 int32_t run_group(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
 {
     int32_t rc;
+    const bool big = J.n_jobs > 4096;
+    if (G.n_lv > 0) { /* explicit ladder: the instantiation with room for KVS_MAX_LEVELS levels */
+        rc = big ? launch_sweep<768, true, 256, kLevelsMax>(J, G, out, st)
+                 : launch_sweep<256, true, 384, kLevelsMax>(J, G, out, st);
+        if (rc != KVS_OK || !J.s)
+            return rc;
+        return big ? launch_sweep<512, false, 128, kLevelsMax>(J, G, out, st)
+                   : launch_sweep<256, false, 256, kLevelsMax>(J, G, out, st);
+    }
     /* Large instances: 12 wavefronts and 256-round windows keep two workgroups (24 wavefronts)
      * on a compute unit next to a 40 KB phase buffer; measured best among the shapes tried. */
-    if (J.n_jobs <= 4096)
-        rc = launch_sweep<256, true, 384>(J, G, out, st);
-    else
-        rc = launch_sweep<768, true, 256>(J, G, out, st);
+    rc = big ? launch_sweep<768, true, 256, kLevelsGeo>(J, G, out, st)
+             : launch_sweep<256, true, 384, kLevelsGeo>(J, G, out, st);
     if (rc != KVS_OK || !J.s)
         return rc;
     /* per-job prompts too wide for one-word entries: second pass over the marked instances */
-    if (J.n_jobs <= 4096)
-        return launch_sweep<256, false, 256>(J, G, out, st);
-    return launch_sweep<512, false, 256>(J, G, out, st);
+    return big ? launch_sweep<512, false, 256, kLevelsGeo>(J, G, out, st)
+               : launch_sweep<256, false, 256, kLevelsGeo>(J, G, out, st);
 }
 
 struct HostPoint {
     uint32_t tau0, k;
     int sched, mode, q;
+    const int32_t *ladder; /* explicit slices, or null for the geometric ladder from tau0 */
+    int n_lv;
 };
 
 /*
@@ -1055,6 +1101,7 @@ struct HostPoint {
  * slices are base * 2^m for a common base (the odd part of tau0) and they
  * have the same mode; a launch holds at most kMaxM shifts and kMaxV variants.
  * A lone invocation of the subroutine has no ladder: its slice is the base.
+ * Points with an explicit ladder share a launch when the ladders are equal.
  */
 int32_t run_points(const JobsDev &J, const HostPoint *pts, int n_pts, const OutsDev &out,
                    hipStream_t st)
@@ -1064,7 +1111,9 @@ int32_t run_points(const JobsDev &J, const HostPoint *pts, int n_pts, const Outs
         if (taken[first])
             continue;
         const int mode = pts[first].mode;
-        const uint32_t base = (mode == MODE_SINGLE)
+        const int32_t *ladder = pts[first].ladder;
+        const uint32_t base = ladder ? (uint32_t)ladder[0]
+                              : (mode == MODE_SINGLE)
                                   ? pts[first].tau0
                                   : pts[first].tau0 >> __builtin_ctz(pts[first].tau0);
         GroupArg G;
@@ -1072,11 +1121,20 @@ int32_t run_points(const JobsDev &J, const HostPoint *pts, int n_pts, const Outs
         G.base = base;
         G.lg_base = (uint8_t)kvs_ilog2_floor(base);
         G.mode = (uint8_t)mode;
+        if (ladder) {
+            G.n_lv = (uint8_t)pts[first].n_lv;
+            for (int l = 0; l < pts[first].n_lv; l++)
+                G.ladder[l] = (uint32_t)ladder[l];
+        }
         for (int i = first; i < n_pts; i++) {
-            if (taken[i] || pts[i].mode != mode)
+            if (taken[i] || pts[i].mode != mode || (pts[i].ladder != nullptr) != (ladder != nullptr))
                 continue;
             uint32_t m = 0;
-            if (mode == MODE_SINGLE) {
+            if (ladder) {
+                if (pts[i].n_lv != pts[first].n_lv ||
+                    memcmp(pts[i].ladder, ladder, sizeof(int32_t) * (size_t)pts[i].n_lv) != 0)
+                    continue;
+            } else if (mode == MODE_SINGLE) {
                 if (pts[i].tau0 != base)
                     continue;
             } else {
@@ -1159,6 +1217,8 @@ int32_t kvs_gba_simulate(const kvs_jobs_t *jobs, const kvs_point_t *pts, int32_t
         hp[q].sched = p.sched;
         hp[q].mode = (p.mode == KVS_MODE_GSA) ? MODE_GSA : MODE_GBA;
         hp[q].q = q;
+        hp[q].ladder = nullptr;
+        hp[q].n_lv = 0;
     }
     OutsDev out{peak, feasible, flow, job_steps, nullptr};
     return run_points(to_dev(jobs, true), hp, n_pts, out, static_cast<hipStream_t>(stream));
@@ -1189,9 +1249,84 @@ int32_t kvs_schedule_eval(const kvs_jobs_t *jobs, const int32_t *tau, const int3
         hp[q].sched = sched[q];
         hp[q].mode = MODE_SINGLE;
         hp[q].q = q;
+        hp[q].ladder = nullptr;
+        hp[q].n_lv = 0;
     }
     OutsDev out{peak, feasible, flow, job_steps, n_completed};
     return run_points(to_dev(jobs, false), hp, n_pts, out, static_cast<hipStream_t>(stream));
+}
+
+int32_t kvs_ladder_simulate(const kvs_jobs_t *jobs, const int32_t *ladders,
+                            const int32_t *n_levels, const int32_t *sched, const int32_t *k,
+                            const int32_t *mode, int32_t n_pts, int64_t *peak, uint8_t *feasible,
+                            int64_t *flow, int64_t *job_steps, void *stream)
+{
+    int32_t rc = check_jobs(jobs);
+    if (rc != KVS_OK)
+        return rc;
+    if (n_pts < 0 || (n_pts > 0 && (!ladders || !n_levels || !sched || !k || !mode)))
+        return KVS_EINVAL;
+    if (n_pts > KVS_MAX_POINTS)
+        return KVS_ELIMIT;
+    if (jobs->n_instances == 0 || n_pts == 0)
+        return KVS_OK;
+    if (!peak || !feasible || !flow)
+        return KVS_EINVAL;
+    HostPoint hp[KVS_MAX_POINTS];
+    for (int32_t q = 0; q < n_pts; q++) {
+        const int32_t *lad = ladders + (size_t)q * KVS_MAX_LEVELS;
+        if (n_levels[q] < 1 || n_levels[q] > KVS_MAX_LEVELS || k[q] < 0 ||
+            (sched[q] != KVS_SCHED_SPS && sched[q] != KVS_SCHED_SIMS) ||
+            (mode[q] != KVS_MODE_GBA && mode[q] != KVS_MODE_GSA))
+            return KVS_EINVAL;
+        for (int32_t l = 0; l < n_levels[q]; l++)
+            if (lad[l] < 1 || (uint32_t)lad[l] > kLenMax || (l > 0 && lad[l] < lad[l - 1]))
+                return KVS_EINVAL;
+        hp[q].tau0 = (uint32_t)lad[0];
+        hp[q].k = (uint32_t)k[q];
+        hp[q].sched = sched[q];
+        hp[q].mode = (mode[q] == KVS_MODE_GSA) ? MODE_GSA : MODE_GBA;
+        hp[q].q = q;
+        hp[q].ladder = lad;
+        hp[q].n_lv = n_levels[q];
+    }
+    OutsDev out{peak, feasible, flow, job_steps, nullptr};
+    return run_points(to_dev(jobs, true), hp, n_pts, out, static_cast<hipStream_t>(stream));
+}
+
+int32_t kvs_paper_ladder(int64_t M, int64_t s, int32_t alpha_num, int32_t alpha_den,
+                         int32_t *ladder, int32_t *n_levels)
+{
+    if (!ladder || !n_levels || s < 0 || M <= s || M - s > (int64_t)kLenMax || alpha_den < 1 ||
+        alpha_num <= alpha_den)
+        return KVS_EINVAL;
+    typedef unsigned __int128 u128;
+    const u128 span = (u128)(M - s);
+    const u128 limit = ((u128)1) << 126; /* no product below may reach it */
+    /* l = max{ j : alpha^j <= M - s }  <=>  num^j <= (M - s) den^j */
+    u128 pn = 1, pd = 1; /* num^l, den^l */
+    int l = 0;
+    for (;;) {
+        if (pn > limit / (u128)alpha_num || pd > limit / ((u128)alpha_den * span))
+            return KVS_ELIMIT;
+        const u128 nn = pn * (u128)alpha_num, nd = pd * (u128)alpha_den;
+        if (nn > span * nd)
+            break;
+        pn = nn;
+        pd = nd;
+        l++;
+        if (l + 1 > KVS_MAX_LEVELS)
+            return KVS_ELIMIT;
+    }
+    /* tau_p = floor(beta alpha^p) = floor((M - s) den^(l-p) / num^(l-p)), p = l, l-1, ..., 0 */
+    u128 an = 1, ad = 1; /* num^(l-p), den^(l-p) */
+    for (int p = l; p >= 0; p--) {
+        ladder[p] = (int32_t)((span * ad) / an);
+        an *= (u128)alpha_num;
+        ad *= (u128)alpha_den;
+    }
+    *n_levels = l + 1;
+    return KVS_OK;
 }
 
 int32_t kvs_validate(const kvs_jobs_t *jobs, void *stream)
@@ -1249,7 +1384,7 @@ const char *kvs_strerror(int32_t status)
     }
 }
 
-int32_t kvs_version(void) { return 200; }
+int32_t kvs_version(void) { return 300; }
 
 /* Host evaluation of the kernels' integer helpers, for the host-side tests. */
 uint32_t kvs_host_class_index(uint32_t x, uint32_t tau0)

@@ -20,7 +20,7 @@ SPS, SIMS = 0, 1
 MODE_GBA, MODE_GSA = 0, 1
 FEASIBLE_EINVAL, FEASIBLE_ERANGE = 0xFE, 0xFF
 OK, EINVAL, EJOB_INFEASIBLE, ERANGE, EHIP, ELIMIT = 0, 1, 2, 3, 4, 5
-MAX_JOBS, MAX_POINTS = 16384, 64
+MAX_JOBS, MAX_POINTS, MAX_LEVELS = 16384, 64, 64
 
 
 class KvsError(RuntimeError):
@@ -59,6 +59,10 @@ def lib():
         L.kvs_schedule_eval.restype = i32
         L.kvs_schedule_eval.argtypes = [C.POINTER(_Jobs), C.POINTER(i32), C.POINTER(i32),
                                         C.POINTER(i32), i32, vp, vp, vp, vp, vp, vp]
+        L.kvs_ladder_simulate.restype = i32
+        L.kvs_ladder_simulate.argtypes = [C.POINTER(_Jobs)] + [C.POINTER(i32)] * 5 + [i32, vp, vp, vp, vp, vp]
+        L.kvs_paper_ladder.restype = i32
+        L.kvs_paper_ladder.argtypes = [C.c_int64, C.c_int64, i32, i32, C.POINTER(i32), C.POINTER(i32)]
         L.kvs_validate.restype = i32
         L.kvs_validate.argtypes = [C.POINTER(_Jobs), vp]
         L.kvs_strerror.restype = C.c_char_p
@@ -146,6 +150,45 @@ def schedule_eval(o: torch.Tensor, s, M: int, tau: Sequence[int], k: Sequence[in
                                    out["feasible"].data_ptr(), out["flow"].data_ptr(),
                                    out["n_completed"].data_ptr(), out["job_steps"].data_ptr(),
                                    _stream(stream)))
+    return out
+
+
+def paper_ladder(M: int, s: int, alpha_num: int, alpha_den: int = 1) -> np.ndarray:
+    """kvs_paper_ladder: the slices floor(beta alpha^p) of Algorithms 1 and 2 (host only)."""
+    lad = np.zeros(MAX_LEVELS, np.int32)
+    n = C.c_int32(0)
+    _check(lib().kvs_paper_ladder(int(M), int(s), int(alpha_num), int(alpha_den),
+                                  lad.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(n)))
+    return lad[:n.value].copy()
+
+
+def ladder_simulate(o: torch.Tensor, s, M: int, ladders, points, o_est: Optional[torch.Tensor] = None,
+                    stream=None) -> dict:
+    """kvs_ladder_simulate.  `ladders`: one 1-d sequence of slices per point;
+    `points`: rows (sched, k, mode)."""
+    pts = np.asarray(points, dtype=np.int32).reshape(-1, 3)
+    P, I = len(pts), o.shape[0]
+    if len(ladders) != P:
+        raise ValueError("one ladder per point")
+    lad = np.zeros((max(P, 1), MAX_LEVELS), np.int32)
+    nlv = np.zeros(max(P, 1), np.int32)
+    for q, l in enumerate(ladders):
+        if len(l) > MAX_LEVELS:
+            raise KvsError(ELIMIT, strerror(ELIMIT))
+        lad[q, :len(l)] = l
+        nlv[q] = len(l)
+    sched, k, mode = (np.ascontiguousarray(pts[:, j]) for j in range(3))
+    out = dict(peak=torch.empty((P, I), dtype=torch.int64, device=o.device),
+               feasible=torch.empty((P, I), dtype=torch.uint8, device=o.device),
+               flow=torch.empty((P, I), dtype=torch.int64, device=o.device),
+               job_steps=torch.empty((P, I), dtype=torch.int64, device=o.device))
+    p32 = C.POINTER(C.c_int32)
+    jobs = _jobs(o, s, M, o_est)
+    _check(lib().kvs_ladder_simulate(C.byref(jobs), lad.ctypes.data_as(p32), nlv.ctypes.data_as(p32),
+                                     sched.ctypes.data_as(p32), k.ctypes.data_as(p32),
+                                     mode.ctypes.data_as(p32), P, out["peak"].data_ptr(),
+                                     out["feasible"].data_ptr(), out["flow"].data_ptr(),
+                                     out["job_steps"].data_ptr(), _stream(stream)))
     return out
 
 

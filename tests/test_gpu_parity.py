@@ -22,7 +22,7 @@ def K():
     assert torch.cuda.is_available(), "these tests need the GPU"
     from paper_2601_22996_amd import kvsched
     kvsched.lib()
-    assert kvsched.version() >= 200
+    assert kvsched.version() >= 300
     return kvsched
 
 
@@ -152,6 +152,65 @@ def test_largest_instance_size(K):
     pts = [(1, 0, 0, 0), (8, 1, 0, 0), (2, 0, 0, 1)]
     assert_same(run_gba(K, o, s, M, pts), O.gba_simulate_batch(o, s, M, pts))
     assert_same(run_gba(K, o, 7, 5000, pts), O.gba_simulate_batch(o, 7, 5000, pts))
+
+
+def run_ladder(K, o, s, M, ladders, pts, o_est=None):
+    s_arg = s if np.isscalar(s) else dev(s)
+    return host(K.ladder_simulate(dev(o), s_arg, M, ladders, pts, o_est=dev(o_est)))
+
+
+@pytest.mark.parametrize("n,I,hetero,est", [(37, 6, False, False), (700, 5, True, True),
+                                            (3000, 3, False, True), (5000, 2, True, False)])
+def test_explicit_ladders(K, n, I, hetero, est):
+    rng = np.random.default_rng(31 * n + I)
+    omax = 900
+    o = np.minimum(rng.geometric(1.0 / 120, (I, n)), omax).astype(np.int32)
+    s = rng.integers(0, 80, (I, n)).astype(np.int32) if hetero else int(rng.integers(0, 80))
+    smax = int(np.max(s))
+    M = smax + 1024
+    e = np.clip(np.rint(o * np.exp(rng.normal(0, 0.6, o.shape))), 1, 1000).astype(np.int32) if est else None
+    # the paper's ladders for three scaling factors, a ladder with repeated and irregular
+    # slices, and one that is the doubling ladder written out
+    ladders = [K.paper_ladder(M, smax, 2), K.paper_ladder(M, smax, 3, 2), K.paper_ladder(M, smax, 4, 3),
+               np.array([1, 1, 3, 3, 3, 10, 11, 50, 200, 200, 1000, 5000], np.int32),
+               np.array([2 << p for p in range(12)], np.int32)]
+    assert ladders[0].tolist() == O.paper_ladder(M, smax, 2).tolist()
+    lads, pts = [], []
+    for lad in ladders:
+        for sched, k, mode in ((0, 0, 0), (1, 0, 0), (0, 0, 1), (1, 5, 1), (0, 3, 0)):
+            lads.append(lad)
+            pts.append((sched, k, mode))
+    got = run_ladder(K, o, s, M, lads, pts, e)
+    want = O.ladder_simulate_batch(o, s, M, lads, pts, e)
+    assert_same(got, want)
+    # the written-out doubling ladder gives what kvs_gba_simulate gives
+    ref = run_gba(K, o, s, M, [(2, sc, k, md) for sc, k, md in pts[-5:]], e)
+    assert_same({k: v[-5:] for k, v in got.items()}, ref)
+
+
+def test_explicit_ladder_edge_cases(K):
+    # a ladder that stops short of some job: that instance is reported in-band
+    o = np.array([[3, 9, 2], [3, 4, 2]], np.int32)
+    got = run_ladder(K, o, 0, 100, [np.array([1, 2, 4], np.int32)], [(0, 0, 0)])
+    assert got["feasible"][0].tolist() == [K.FEASIBLE_EINVAL, 1]
+    assert got["flow"][0, 1] == O.ladder_simulate(o[1], 0, 100, [1, 2, 4])["flow"]
+    # the two-point experiment of the paper's appendix on its own ladder, both extreme orders
+    lad = K.paper_ladder(256, 96, 2)
+    oo = np.array([[160] * 6 + [1] * 194, [1] * 194 + [160] * 6], np.int32)
+    got = run_ladder(K, oo, 96, 256, [lad], [(0, 0, 1)])
+    assert got["flow"][0].tolist() == [18542, 17960]
+    # wide prompts (two-word entries) with 64 levels
+    rng = np.random.default_rng(3)
+    o = rng.integers(1, 3000, (3, 500)).astype(np.int32)
+    s = rng.integers(0, 2 ** 22, (3, 500)).astype(np.int32)
+    lad = np.unique(np.rint(1.16 ** np.arange(1, 60)).astype(np.int64))
+    lad = np.append(lad[lad < 5000], 5000).astype(np.int32)
+    assert 48 < len(lad) <= K.MAX_LEVELS
+    pts = [(0, 0, 0), (1, 0, 1)]
+    assert_same(run_ladder(K, o, s, 2 ** 24, [lad, lad], pts),
+                O.ladder_simulate_batch(o, s, 2 ** 24, [lad, lad], pts))
+    with pytest.raises(K.KvsError):
+        K.ladder_simulate(dev(o), dev(s), 2 ** 24, [np.array([4, 2], np.int32)], [(0, 0, 0)])
 
 
 def test_long_phases_cross_many_windows(K):

@@ -106,3 +106,37 @@ def test_kstar_matches_scan_of_the_peak_formula(L):
             k += 1
         assert L.kvs_host_kstar(tau, s, M) == k, (tau, s, M)
     assert L.kvs_host_kstar(1, 0, 2 ** 39) == 2 ** 39
+
+
+def test_paper_ladder_matches_the_oracle_and_the_definition(L):
+    import numpy as np
+    import oracle as O
+    L.kvs_paper_ladder.restype = C.c_int32
+    L.kvs_paper_ladder.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32,
+                                   C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+
+    def lib_ladder(M, s, num, den):
+        lad = (C.c_int32 * 64)()
+        n = C.c_int32(0)
+        rc = L.kvs_paper_ladder(M, s, num, den, lad, C.byref(n))
+        return rc, list(lad[:n.value])
+
+    from fractions import Fraction
+    rnd = random.Random(11)
+    for _ in range(300):
+        num, den = rnd.choice([(2, 1), (3, 2), (4, 3), (3, 1), (7, 4), (5, 3)])
+        s = rnd.randint(0, 5000)
+        M = s + rnd.randint(1, 2 ** rnd.randint(1, 20))
+        rc, got = lib_ladder(M, s, num, den)
+        assert rc == 0
+        a = Fraction(num, den)
+        ell = 0
+        while a ** (ell + 1) <= M - s:
+            ell += 1
+        beta = Fraction(M - s) / a ** ell
+        assert 1 <= beta < a
+        want = [int(beta * a ** p) for p in range(ell + 1)]       # floor of an exact rational
+        assert got == want == O.paper_ladder(M, s, num, den).tolist()
+        assert got[-1] == M - s
+    assert lib_ladder(10, 10, 2, 1)[0] == 1 and lib_ladder(10, 0, 1, 1)[0] == 1
+    assert lib_ladder(2 ** 30, 0, 4, 3)[0] == 5                    # needs more than 64 levels

@@ -455,3 +455,67 @@ def test_estimate_clamp_reading():
     # clamped to M instead of M - s in the slice 24.
     r = O.gba_simulate([1, 1], 4, 16, tau0=3, o_est=[100, 100])
     assert r["flow"] == 1 + 13 and r["n_phases"] == 1 and r["job_steps"] == 2
+
+
+# --------------------------------------------------------------------------
+# The paper's own ladder (any scaling factor): floor(beta alpha^p)
+# --------------------------------------------------------------------------
+def test_two_point_experiment_bracket():
+    # Appendix "Numerical Experiments", two-point distribution: s = 96, six jobs with o = 160
+    # and 194 with o = 1, M = 256; the figure prints 18268 for GSA with alpha = 2.  The order
+    # of the jobs is not printed; the value must lie between the orders "long jobs last" and
+    # "long jobs first".  Ladder: l = 7, beta = 160/128, slices 1 2 5 10 20 40 80 160.
+    lad = O.paper_ladder(256, 96, 2)
+    assert lad.tolist() == [1, 2, 5, 10, 20, 40, 80, 160]
+    o = [160] * 6 + [1] * 194
+    first = O.ladder_simulate(o, 96, 256, lad, mode=O.MODE_GSA)
+    last = O.ladder_simulate(o[::-1], 96, 256, lad, mode=O.MODE_GSA)
+    assert last["flow"] <= 18268 <= first["flow"]
+    assert (last["flow"], first["flow"]) == (17960, 18542)
+    assert first["peak"] <= 256 and last["peak"] <= 256
+    # the clairvoyant counterpart on the same ladder is cheaper
+    assert O.ladder_simulate(o, 96, 256, lad)["flow"] <= last["flow"]
+
+
+def test_ladder_form_agrees_with_the_doubling_form():
+    rng = np.random.default_rng(8)
+    for _ in range(30):
+        n = int(rng.integers(1, 80))
+        o = rng.integers(1, 300, n).astype(np.int32)
+        s = int(rng.integers(0, 30))
+        tau0 = int(rng.choice([1, 2, 3, 8]))
+        lad = [tau0 << p for p in range(12)]
+        for mode in (O.MODE_GBA, O.MODE_GSA):
+            for sched in (O.SPS, O.SIMS):
+                assert O.ladder_simulate(o, s, 4000, lad, sched, 0, mode) == \
+                    O.gba_simulate(o, s, 4000, tau0, sched, 0, mode)
+    with pytest.raises(O.OracleError):
+        O.ladder_simulate([9], 0, 100, [1, 2, 4])          # no slice covers the job
+    with pytest.raises(O.OracleError):
+        O.ladder_simulate([1], 0, 100, [2, 1])             # not a ladder
+
+
+@pytest.mark.parametrize("num,den,gamma_num,gamma_den", [(2, 1, 16, 1), (3, 2, 45, 4), (4, 3, 32, 3)])
+def test_gba_ratio_theorem_on_the_papers_ladder(num, den, gamma_num, gamma_den):
+    # Theorem "Approximation Guarantee of GBA" with k_min >= 1:
+    # GBA <= (3 alpha^2 + alpha + alpha/(alpha-1)) OPT: 16, 11.25 and 32/3 for alpha = 2, 3/2, 4/3;
+    # GSA <= (2 + 2/(alpha-1)) times that.
+    from fractions import Fraction
+    a = Fraction(num, den)
+    assert 3 * a * a + a + a / (a - 1) == Fraction(gamma_num, gamma_den)
+    rng = np.random.default_rng(num * 10 + den)
+    for _ in range(20):
+        s = int(rng.integers(0, 5))
+        M = s + int(rng.integers(8, 40))
+        n = int(rng.integers(1, 6))
+        o = rng.integers(1, min(8, M - s) + 1, n).astype(np.int32)
+        lad = O.paper_ladder(M, s, num, den)
+        opt = O.opt_exact(o, s, M)
+        gba = O.ladder_simulate(o, s, M, lad)
+        gsa = O.ladder_simulate(o, s, M, lad, mode=O.MODE_GSA)
+        assert gba["feasible"] == 1 and gsa["feasible"] == 1
+        assert gba["flow"] * gamma_den <= gamma_num * opt
+        assert Fraction(gsa["flow"]) <= (2 + 2 / (a - 1)) * Fraction(gamma_num, gamma_den) * opt
+        # the parallelism never grows with the slice (used in the GSA analysis)
+        ks = [max(1, O.kstar(int(t), s, M)) for t in lad]
+        assert all(ks[i] >= ks[i + 1] for i in range(len(ks) - 1))
