@@ -279,8 +279,10 @@ __device__ __forceinline__ unsigned long long wave_sum_u63(unsigned long long v)
  * duration, with the field width taken from the instance's largest values;
  * two words when that does not fit 32 bits. */
 struct EntryFmt {
-    uint32_t dbits; /* duration in bits [0, dbits), done-bit at dbits, prompt above */
-    bool has_s;     /* per-job prompts are stored at all                             */
+    uint32_t dbits;  /* duration in bits [0, dbits), done-bit at dbits, prompt above          */
+    uint32_t sshift; /* where the prompt starts: dbits + 1, or dbits when no done-bit is kept */
+    bool has_s;      /* per-job prompts are stored at all                                     */
+    bool all_done;   /* every run completes: no done-bit                                      */
 };
 
 template <bool PACKED>
@@ -288,9 +290,11 @@ __device__ __forceinline__ void put_entry(uint32_t *buf, uint32_t n_cap, uint32_
                                           bool done, uint32_t s, const EntryFmt &F)
 {
     if (PACKED) {
-        uint32_t w = d | ((uint32_t)done << F.dbits);
+        uint32_t w = d;
+        if (!F.all_done)
+            w |= (uint32_t)done << F.dbits;
         if (F.has_s)
-            w |= s << (F.dbits + 1);
+            w |= s << F.sshift;
         buf[pos] = w;
     } else {
         buf[pos] = d | ((uint32_t)done << 31);
@@ -306,8 +310,8 @@ __device__ __forceinline__ void get_entry(const uint32_t *buf, uint32_t n_cap, u
     const uint32_t w = buf[pos];
     if (PACKED) {
         d = w & ((1u << F.dbits) - 1u);
-        done = (w >> F.dbits) & 1u;
-        s = F.has_s ? (w >> (F.dbits + 1)) : s_scalar;
+        done = F.all_done || ((w >> F.dbits) & 1u);
+        s = F.has_s ? (w >> F.sshift) : s_scalar;
     } else {
         d = w & 0x7fffffffu;
         done = w >> 31;
@@ -492,8 +496,9 @@ __device__ __forceinline__ void eval_sparse(const Slot &sl, const Sched &sc, boo
         pk = (int32_t)occ;
 }
 
+/* 768 threads: two workgroups per compute unit need 6 wavefronts per SIMD, i.e. at most 80 VGPRs. */
 template <int T, bool PACKED, int WIN, int LV>
-__global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, OutsDev out)
+__global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDev J, GroupArg G, OutsDev out)
 {
     constexpr int NW = T / 64;
     constexpr int kLevels = LV;          /* levels of the ladder this instantiation can hold */
@@ -513,6 +518,7 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
     __shared__ Slot slot[kSlots];
     __shared__ Sched sched[kMaxV][kSlots];
     __shared__ Result res[kMaxV][kSlots];
+    __shared__ uint32_t wkeep[NW]; /* per wavefront: entries its stretch keeps in a partition */
     __shared__ unsigned long long sumO_sh;
     __shared__ uint32_t flags, maxO_sh, maxS_sh, maxE_sh;
 
@@ -583,6 +589,8 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
                 mxO = v.o > mxO ? v.o : mxO;
                 mxS = v.s > mxS ? v.s : mxS;
                 mxG = v.gb > mxG ? v.gb : mxG;
+                if (PACKED && one_phase_each) /* the job as a phase entry, at its place in the input */
+                    buf[i] = per_job_s ? ((v.s << 16) | (v.o & 0xffffu)) : v.o;
                 atomicAdd(&cumE[wave][v.ga], 1u); /* the wavefront's own histogram */
                 if (!one_phase_each)
                     atomicAdd(&cumL[wave][v.gb], 1u);
@@ -646,8 +654,18 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
     __syncthreads();
 
     /* ---- entry format: does prompt | done | duration fit one word? ---- */
+    /* One phase per job and values narrow enough for the copy pass 1 left in LDS (duration in
+     * 16 bits under a 16-bit prompt, or a bare duration): every phase's entries are then cut out
+     * of that copy inside LDS and the jobs are not read from memory again. */
+    const bool nested = PACKED && one_phase_each && G.mode != MODE_SINGLE &&
+                        (!per_job_s || (maxO_sh < 65536u && maxS_sh < 65536u));
     EntryFmt F;
-    {
+    if (nested) {
+        F.dbits = per_job_s ? 16u : 31u;
+        F.sshift = F.dbits;
+        F.has_s = per_job_s;
+        F.all_done = true;
+    } else {
         /* durations are at most max(o), or a slice of a level some job reaches */
         uint64_t dmax = lad[maxE_sh];
         const uint64_t tau_m = lad[G.m[G.n_m - 1]];
@@ -658,7 +676,9 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
         if (dmax > 0x7fffffffull)
             dmax = 0x7fffffffull; /* such a phase is out of range anyway */
         F.dbits = 32u - kvs_clz32((uint32_t)dmax);
+        F.sshift = F.dbits + 1u;
         F.has_s = per_job_s && maxS_sh > 0; /* all-zero prompts need no field */
+        F.all_done = false;
         const uint32_t sbits = F.has_s ? 32u - kvs_clz32(maxS_sh) : 0u;
         const bool fits = F.dbits + 1u + sbits <= 32u;
         if (PACKED && !fits && flags == 0) {
@@ -874,8 +894,140 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
         }
     };
 
+    /* Chunks of 64 entries a wavefront holds in registers while LDS is rearranged under it. */
+    constexpr int kHold = (T == 256) ? 16 : (KVS_MAX_JOBS + T - 1) / T;
+    const uint32_t dmask = (F.dbits >= 32u) ? 0xffffffffu : ((1u << F.dbits) - 1u);
+
+    /* Stable partition of buf[0 .. cnt): entries with duration <= theta keep their order at
+     * the front, the others follow, also in order.  Each wavefront takes a stretch, holds it
+     * in registers across the barrier and writes it back to its two destinations. */
+    auto split_front = [&](uint32_t cnt, uint32_t theta) {
+        const uint32_t span = ((cnt + NW - 1) / NW + 63u) & ~63u;
+        const uint32_t lo = (uint32_t)wave * span < cnt ? (uint32_t)wave * span : cnt;
+        const uint32_t hi = lo + span < cnt ? lo + span : cnt;
+        uint32_t held[kHold];
+        uint32_t kept = 0;
+#pragma unroll
+        for (int c = 0; c < kHold; c++) {
+            const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
+            held[c] = (idx < hi) ? buf[idx] : 0xffffffffu;
+            kept += (uint32_t)__popcll(__ballot(idx < hi && (held[c] & dmask) <= theta));
+        }
+        if (lane == 0)
+            wkeep[wave] = kept;
+        __syncthreads();
+        uint32_t front = 0, back = 0; /* where this wavefront's kept / moved entries begin */
+        for (int w = 0; w < NW; w++) {
+            const uint32_t wlo = (uint32_t)w * span < cnt ? (uint32_t)w * span : cnt;
+            const uint32_t whi = wlo + span < cnt ? wlo + span : cnt;
+            const uint32_t kw = wkeep[w];
+            if (w < wave) {
+                front += kw;
+                back += (whi - wlo) - kw;
+            }
+            back += kw; /* the moved entries start after everything that is kept */
+        }
+#pragma unroll
+        for (int c = 0; c < kHold; c++) {
+            const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
+            const bool act = idx < hi;
+            const bool keep = act && (held[c] & dmask) <= theta;
+            const uint64_t bk = __ballot(keep), bm = __ballot(act && !keep);
+            if (act)
+                buf[keep ? front + lanes_below(bk) : back + lanes_below(bm)] = held[c];
+            front += (uint32_t)__popcll(bk);
+            back += (uint32_t)__popcll(bm);
+        }
+        __syncthreads();
+    };
+
+    /* Stable multisplit by level of buf[b0 .. n) (entries above every merged phase, in input
+     * order) to where the level slots expect them.  cumL serves as per-wavefront histogram. */
+    auto split_tail = [&](uint32_t b0) {
+        const uint32_t cnt = n - b0;
+        const uint32_t span = ((cnt + NW - 1) / NW + 63u) & ~63u;
+        const uint32_t lo = b0 + ((uint32_t)wave * span < cnt ? (uint32_t)wave * span : cnt);
+        const uint32_t hi = (lo + span < n) ? lo + span : n;
+        for (int i = tid; i < NW * kLevels; i += T)
+            (&cumL[0][0])[i] = 0;
+        __syncthreads();
+        uint32_t held[kHold]; /* the levels are worked out twice rather than held as well */
+#pragma unroll
+        for (int c = 0; c < kHold; c++) {
+            const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
+            held[c] = 0;
+            if (idx < hi) {
+                bool ok = true; /* checked in pass 1 */
+                held[c] = buf[idx];
+                atomicAdd(&cumL[wave][level_of<EXPLICIT>(held[c] & dmask, G, lad, ok)], 1u);
+            }
+        }
+        __syncthreads();
+        uint32_t cur = 0; /* lane l: next free position of level l for this wavefront */
+        if (lane < kLevels) {
+            cur = slot[lane].off;
+            for (int w = 0; w < wave; w++)
+                cur += cumL[w][lane];
+        }
+#pragma unroll
+        for (int c = 0; c < kHold; c++) {
+            const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
+            const bool act = idx < hi;
+            bool ok = true;
+            const uint32_t lv = act ? level_of<EXPLICIT>(held[c] & dmask, G, lad, ok) : 0u;
+            uint32_t pos = 0;
+            uint64_t todo = __ballot(act);
+            while (todo) {
+                const int src = __ffsll((unsigned long long)todo) - 1;
+                const uint32_t c0 = __builtin_amdgcn_readlane(lv, src);
+                const uint64_t mk = __ballot(act && lv == c0);
+                const uint32_t b = __builtin_amdgcn_readlane(cur, (int)c0);
+                if (act && lv == c0)
+                    pos = b + lanes_below(mk);
+                if ((uint32_t)lane == c0)
+                    cur += (uint32_t)__popcll(mk);
+                todo &= ~mk;
+            }
+            if (act)
+                buf[pos] = held[c];
+        }
+        __syncthreads();
+    };
+
     if (!bad) {
-        if (one_phase_each && G.mode != MODE_SINGLE) {
+        if (nested) {
+/* ---- every phase is cut out of the LDS copy of the instance ---- */
+            const uint32_t m_max = G.m[G.n_m - 1];
+            uint32_t cnt = 0; /* jobs of the levels up to m_max: the largest merged phase */
+            for (uint32_t l = 0; l <= m_max; l++)
+                cnt += totE[l];
+            if (cnt < n) {
+                if (cnt > 0)
+                    split_front(n, lad[m_max]);
+                split_tail(cnt);
+            }
+            int mi = (int)G.n_m - 1;
+            for (uint32_t g = m_max;; g--) {
+                /* buf[0 .. cnt) holds the jobs of the levels 0 .. g in input order */
+                if (mi >= 0 && G.m[mi] == g) {
+                    const int si = kLevels + mi;
+                    if (slot[si].n > 0 && slot[si].alias == (uint32_t)si) {
+                        eval_slot(si);
+                        __syncthreads();
+                    }
+                    mi--;
+                }
+                if (g == m_min)
+                    break;
+                const uint32_t below = cnt - totE[g];
+                if (totE[g] > 0 && below > 0)
+                    split_front(cnt, lad[g - 1]); /* level g's jobs move behind the lower levels' */
+                cnt = below;
+            }
+            for (int si = (int)m_min + 1; si < kLevels; si++)
+                eval_slot(si);
+            __syncthreads();
+        } else if (one_phase_each && G.mode != MODE_SINGLE) {
             /* ---- stable multisplit by level: every level's jobs side by side, input order ---- */
             uint32_t cur = 0; /* lane l: next free position of level l for this wavefront */
             if (lane < kLevels) {
@@ -934,8 +1086,8 @@ __global__ __launch_bounds__(T) void kvs_sweep_kernel(JobsDev J, GroupArg G, Out
                 __syncthreads();
             }
         }
-        /* ---- merged first phases, one per shift ---- */
-        for (int mi = 0; mi < (int)G.n_m; mi++) {
+        /* ---- merged first phases, one per shift (the LDS-only path has done them) ---- */
+        for (int mi = 0; mi < (int)G.n_m && !nested; mi++) {
             const int si = kLevels + mi;
             if (slot[si].n == 0 || slot[si].alias != (uint32_t)si)
                 continue;
