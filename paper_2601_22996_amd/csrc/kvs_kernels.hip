@@ -497,7 +497,7 @@ __device__ __forceinline__ void eval_sparse(const Slot &sl, const Sched &sc, boo
 }
 
 /* 768 threads: two workgroups per compute unit need 6 wavefronts per SIMD, i.e. at most 80 VGPRs. */
-template <int T, bool PACKED, int WIN, int LV>
+template <int T, bool PACKED, int WIN, int LV, int HOLD>
 __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDev J, GroupArg G, OutsDev out)
 {
     constexpr int NW = T / 64;
@@ -895,7 +895,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
     };
 
     /* Chunks of 64 entries a wavefront holds in registers while LDS is rearranged under it. */
-    constexpr int kHold = (T == 256) ? 16 : (KVS_MAX_JOBS + T - 1) / T;
+    constexpr int kHold = HOLD; /* the launch guarantees n_jobs <= HOLD * T */
     const uint32_t dmask = (F.dbits >= 32u) ? 0xffffffffu : ((1u << F.dbits) - 1u);
 
     /* Stable partition of buf[0 .. cnt): entries with duration <= theta keep their order at
@@ -1206,11 +1206,12 @@ JobsDev to_dev(const kvs_jobs_t *jobs, bool use_estimates)
     return J;
 }
 
-template <int T, bool PACKED, int WIN, int LV>
+template <int T, bool PACKED, int WIN, int LV, int HOLD>
 int32_t launch_sweep(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
 {
     const size_t lds = sizeof(uint32_t) * (size_t)J.n_jobs * (PACKED ? 1 : 2);
-    auto kern = kvs_sweep_kernel<T, PACKED, WIN, LV>;
+    static_assert(!PACKED || HOLD * T >= (T == 256 ? 4096 : 1), "hold");
+    auto kern = kvs_sweep_kernel<T, PACKED, WIN, LV, HOLD>;
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return KVS_EHIP;
@@ -1222,23 +1223,27 @@ int32_t run_group(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipSt
 {
     int32_t rc;
     const bool big = J.n_jobs > 4096;
+    /* registers a thread needs to hold its share of an instance: n_jobs / threads, rounded up */
+    constexpr int kHoldMid = 14, kHoldMax = (KVS_MAX_JOBS + 767) / 768;
+    const bool mid = J.n_jobs <= kHoldMid * 768;
     if (G.n_lv > 0) { /* explicit ladder: the instantiation with room for KVS_MAX_LEVELS levels */
-        rc = big ? launch_sweep<768, true, 256, kLevelsMax>(J, G, out, st)
-                 : launch_sweep<256, true, 384, kLevelsMax>(J, G, out, st);
+        rc = big ? launch_sweep<768, true, 256, kLevelsMax, kHoldMax>(J, G, out, st)
+                 : launch_sweep<256, true, 384, kLevelsMax, 16>(J, G, out, st);
         if (rc != KVS_OK || !J.s)
             return rc;
-        return big ? launch_sweep<512, false, 128, kLevelsMax>(J, G, out, st)
-                   : launch_sweep<256, false, 256, kLevelsMax>(J, G, out, st);
+        return big ? launch_sweep<512, false, 128, kLevelsMax, 1>(J, G, out, st)
+                   : launch_sweep<256, false, 256, kLevelsMax, 1>(J, G, out, st);
     }
     /* Large instances: 12 wavefronts and 256-round windows keep two workgroups (24 wavefronts)
      * on a compute unit next to a 40 KB phase buffer; measured best among the shapes tried. */
-    rc = big ? launch_sweep<768, true, 256, kLevelsGeo>(J, G, out, st)
-             : launch_sweep<256, true, 384, kLevelsGeo>(J, G, out, st);
+    rc = !big ? launch_sweep<256, true, 384, kLevelsGeo, 16>(J, G, out, st)
+         : mid ? launch_sweep<768, true, 256, kLevelsGeo, kHoldMid>(J, G, out, st)
+               : launch_sweep<768, true, 256, kLevelsGeo, kHoldMax>(J, G, out, st);
     if (rc != KVS_OK || !J.s)
         return rc;
     /* per-job prompts too wide for one-word entries: second pass over the marked instances */
-    return big ? launch_sweep<512, false, 256, kLevelsGeo>(J, G, out, st)
-               : launch_sweep<256, false, 256, kLevelsGeo>(J, G, out, st);
+    return big ? launch_sweep<512, false, 256, kLevelsGeo, 1>(J, G, out, st)
+               : launch_sweep<256, false, 256, kLevelsGeo, 1>(J, G, out, st);
 }
 
 struct HostPoint {
