@@ -909,6 +909,8 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         uint32_t kept = 0;
 #pragma unroll
         for (int c = 0; c < kHold; c++) {
+            if (lo + (uint32_t)c * 64u >= hi)
+                break; /* the rest of the stretch is empty (the same for all lanes) */
             const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
             held[c] = (idx < hi) ? buf[idx] : 0xffffffffu;
             kept += (uint32_t)__popcll(__ballot(idx < hi && (held[c] & dmask) <= theta));
@@ -929,6 +931,8 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         }
 #pragma unroll
         for (int c = 0; c < kHold; c++) {
+            if (lo + (uint32_t)c * 64u >= hi)
+                break; /* the rest of the stretch is empty (the same for all lanes) */
             const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
             const bool act = idx < hi;
             const bool keep = act && (held[c] & dmask) <= theta;
@@ -954,6 +958,8 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         uint32_t held[kHold]; /* the levels are worked out twice rather than held as well */
 #pragma unroll
         for (int c = 0; c < kHold; c++) {
+            if (lo + (uint32_t)c * 64u >= hi)
+                break; /* the rest of the stretch is empty (the same for all lanes) */
             const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
             held[c] = 0;
             if (idx < hi) {
@@ -971,6 +977,8 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         }
 #pragma unroll
         for (int c = 0; c < kHold; c++) {
+            if (lo + (uint32_t)c * 64u >= hi)
+                break; /* the rest of the stretch is empty (the same for all lanes) */
             const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
             const bool act = idx < hi;
             bool ok = true;
