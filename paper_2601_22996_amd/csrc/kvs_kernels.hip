@@ -825,12 +825,11 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
                 }
                 next_item += 1;
             } else {
-                for (uint32_t j = 0; j < sc.nslab; j++) {
-                    if ((next_item + j) % NW == (uint32_t)wave) {
-                        eval_slab<PACKED>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk,
-                                          sumF);
-                        mine = true;
-                    }
+                /* this wavefront's slabs: every NW-th, starting where the dealing has got to */
+                const uint32_t first = ((uint32_t)wave + NW - next_item % NW) % NW;
+                for (uint32_t j = first; j < sc.nslab; j += NW) {
+                    eval_slab<PACKED>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk, sumF);
+                    mine = true;
                 }
                 next_item += sc.nslab;
             }
