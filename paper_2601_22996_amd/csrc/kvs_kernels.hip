@@ -58,6 +58,7 @@ struct JobsDev {
     int32_t n_inst;
     int32_t n_jobs;
     uint32_t s_scalar;
+    uint32_t vec4; /* rows are 16-byte aligned and n_jobs is a multiple of 4: 128-bit loads allowed */
     uint64_t M;
 };
 
@@ -539,7 +540,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
     }
 
     /* each wavefront owns a contiguous segment of the jobs */
-    const uint32_t seg = ((n + NW - 1) / NW + 63u) & ~63u;
+    const uint32_t seg = ((n + NW - 1) / NW + 255u) & ~255u; /* whole 256-job chunks */
     const uint32_t seg_lo = (uint32_t)wave * seg < n ? (uint32_t)wave * seg : n;
     const uint32_t seg_hi = seg_lo + seg < n ? seg_lo + seg : n;
 
@@ -572,35 +573,70 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         uint32_t mxO = 0, mxS = 0, mxG = 0;
         bool inval = false;
         const bool want_e = (G.mode == MODE_GBA) && (J.e != nullptr);
-        RawJob nxt;
-        nxt.o = nxt.s = nxt.e = 1;
-        if (seg_lo + lane < seg_hi)
-            nxt = load_job(J, row + seg_lo + lane, want_e);
-        for (uint32_t base = seg_lo; base < seg_hi; base += 64) {
-            const uint32_t i = base + lane;
-            const RawJob raw = nxt;
-            if (i + 64 < seg_hi) /* the next chunk's loads fly while this one is classified */
-                nxt = load_job(J, row + i + 64, want_e);
-            if (i < seg_hi) {
-                const JobView v = view_job<EXPLICIT>(raw, J, G, lad);
-                inval |= !v.valid;
-                if (G.mode != MODE_SINGLE || v.go == 0)
-                    sumO += v.o; /* every job completes once; a lone invocation completes o <= tau */
-                mxO = v.o > mxO ? v.o : mxO;
-                mxS = v.s > mxS ? v.s : mxS;
-                mxG = v.gb > mxG ? v.gb : mxG;
-                if (PACKED && one_phase_each) /* the job as a phase entry, at its place in the input */
-                    buf[i] = per_job_s ? ((v.s << 16) | (v.o & 0xffffu)) : v.o;
-                atomicAdd(&cumE[wave][v.ga], 1u); /* the wavefront's own histogram */
-                if (!one_phase_each)
-                    atomicAdd(&cumL[wave][v.gb], 1u);
-                if (per_job_s) { /* the maxima settle after a few jobs; then this only reads */
-                    if (v.s > sMaxEnter[v.ga])
-                        atomicMax(&sMaxEnter[v.ga], v.s);
-                    for (uint32_t l = v.ga; l <= v.gb; l++)
-                        if (v.s > sMaxPart[l])
-                            atomicMax(&sMaxPart[l], v.s);
+        auto account = [&](const RawJob &raw, uint32_t i) {
+            const JobView v = view_job<EXPLICIT>(raw, J, G, lad);
+            inval |= !v.valid;
+            if (G.mode != MODE_SINGLE || v.go == 0)
+                sumO += v.o; /* every job completes once; a lone invocation completes o <= tau */
+            mxO = v.o > mxO ? v.o : mxO;
+            mxS = v.s > mxS ? v.s : mxS;
+            mxG = v.gb > mxG ? v.gb : mxG;
+            if (PACKED && one_phase_each) /* the job as a phase entry, at its place in the input */
+                buf[i] = per_job_s ? ((v.s << 16) | (v.o & 0xffffu)) : v.o;
+            atomicAdd(&cumE[wave][v.ga], 1u); /* the wavefront's own histogram */
+            if (!one_phase_each)
+                atomicAdd(&cumL[wave][v.gb], 1u);
+            if (per_job_s) { /* the maxima settle after a few jobs; then this only reads */
+                if (v.s > sMaxEnter[v.ga])
+                    atomicMax(&sMaxEnter[v.ga], v.s);
+                for (uint32_t l = v.ga; l <= v.gb; l++)
+                    if (v.s > sMaxPart[l])
+                        atomicMax(&sMaxPart[l], v.s);
+            }
+        };
+        if (J.vec4) {
+            /* Four consecutive jobs per lane and 16-byte loads: pass 1 is bound by how many bytes a
+             * wavefront keeps in flight, and nothing here depends on which lane sees which job.
+             * (n_jobs and the segment bounds are multiples of 4, the rows 16-byte aligned.) */
+            struct Quad {
+                int4 o, s, e;
+            };
+            auto load4 = [&](uint32_t i) {
+                Quad q;
+                q.o = *reinterpret_cast<const int4 *>(J.o + row + i);
+                q.s = J.s ? *reinterpret_cast<const int4 *>(J.s + row + i)
+                          : make_int4((int)J.s_scalar, (int)J.s_scalar, (int)J.s_scalar, (int)J.s_scalar);
+                q.e = want_e ? *reinterpret_cast<const int4 *>(J.e + row + i) : make_int4(1, 1, 1, 1);
+                return q;
+            };
+            Quad nxt;
+            nxt.o = nxt.s = nxt.e = make_int4(1, 1, 1, 1);
+            if (seg_lo + 4u * lane < seg_hi)
+                nxt = load4(seg_lo + 4u * lane);
+            for (uint32_t base = seg_lo; base < seg_hi; base += 256) {
+                const uint32_t i = base + 4u * (uint32_t)lane;
+                const Quad cur = nxt;
+                if (i + 256 < seg_hi) /* the next chunk's loads fly while this one is classified */
+                    nxt = load4(i + 256);
+                if (i < seg_hi) {
+                    account(RawJob{cur.o.x, cur.s.x, cur.e.x}, i);
+                    account(RawJob{cur.o.y, cur.s.y, cur.e.y}, i + 1);
+                    account(RawJob{cur.o.z, cur.s.z, cur.e.z}, i + 2);
+                    account(RawJob{cur.o.w, cur.s.w, cur.e.w}, i + 3);
                 }
+            }
+        } else {
+            RawJob nxt;
+            nxt.o = nxt.s = nxt.e = 1;
+            if (seg_lo + lane < seg_hi)
+                nxt = load_job(J, row + seg_lo + lane, want_e);
+            for (uint32_t base = seg_lo; base < seg_hi; base += 64) {
+                const uint32_t i = base + lane;
+                const RawJob raw = nxt;
+                if (i + 64 < seg_hi) /* the next chunk's loads fly while this one is classified */
+                    nxt = load_job(J, row + i + 64, want_e);
+                if (i < seg_hi)
+                    account(raw, i);
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -1210,6 +1246,9 @@ JobsDev to_dev(const kvs_jobs_t *jobs, bool use_estimates)
     J.n_jobs = jobs->n_jobs;
     J.s_scalar = jobs->s ? 0u : (uint32_t)jobs->s_scalar;
     J.M = (uint64_t)jobs->M;
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(J.o) | reinterpret_cast<uintptr_t>(J.s) |
+                           reinterpret_cast<uintptr_t>(J.e);
+    J.vec4 = (jobs->n_jobs % 4 == 0 && bits % 16 == 0) ? 1u : 0u;
     return J;
 }
 
