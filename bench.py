@@ -38,18 +38,24 @@ def kernel_source_digest():
     return h.hexdigest()
 
 
-def measured_traffic(workload_name):
-    """HBM bytes per launch from the committed rocprofv3 --pmc note, or None when the note is
-    for another workload or the kernel sources have changed since it was taken."""
+def measured_counters(workload_name):
+    """The key: value lines of the committed rocprofv3 --pmc note, or {} when the note is for
+    another workload or the kernel sources have changed since the counters were taken."""
     try:
         text = open(TRAFFIC_NOTE).read()
     except OSError:
-        return None
+        return {}
     kv = dict(line.strip("- ").split(": ", 1) for line in text.splitlines()
               if line.startswith("- ") and ": " in line)
     if kv.get("workload") != workload_name or kv.get("source_sha256") != kernel_source_digest():
-        return None
-    return int(kv["traffic_bytes_per_launch"])
+        return {}
+    return kv
+
+
+def measured_traffic(workload_name):
+    """HBM bytes per launch (scaled FETCH_SIZE + WRITE_SIZE), or None."""
+    kv = measured_counters(workload_name)
+    return int(kv["traffic_bytes_per_launch"]) if "traffic_bytes_per_launch" in kv else None
 
 
 def load_workload(w, torch, threads):
@@ -73,25 +79,43 @@ def load_workload(w, torch, threads):
     return o, s, e
 
 
-def cpu_baseline(w, target_seconds):
-    """The oracle as it stands, single-threaded, on the first instances of the workload."""
+def cpu_baseline(w, target_seconds, threads):
+    """The oracle as it stands on the first instances of the workload: first on one core, then
+    one oracle call per thread over disjoint instance ranges (instances are independent; the
+    oracle itself is single-threaded and the C call releases the interpreter lock)."""
     import oracle as O
+    from concurrent.futures import ThreadPoolExecutor
     from paper_2601_22996_amd import workloads as W
     pts = w.sweep()
     probe = min(4, w.n_instances)
-    d = W.generate(w, 0, min(w.n_instances, 2048))
+    d = W.generate(w, 0, min(w.n_instances, 4096))
+    avail = d["o"].shape[0]
     sarg = d["s"] if d["s"] is not None else d["s_scalar"]
+
+    def run(i0, i1):
+        return int(O.gba_simulate_batch(d["o"], sarg, d["M"], pts, d["o_est"], i0, i1)["job_steps"].sum())
+
     t = time.perf_counter()
-    r = O.gba_simulate_batch(d["o"], sarg, d["M"], pts, d["o_est"], 0, probe)
-    dt = max(time.perf_counter() - t, 1e-6)
-    cnt = int(max(probe, min(d["o"].shape[0], probe * target_seconds / dt)))
+    run(0, probe)
+    per_inst = max(time.perf_counter() - t, 1e-6) / probe
+    half = target_seconds / 2
+    cnt1 = int(max(probe, min(avail, half / per_inst)))
     t = time.perf_counter()
-    r = O.gba_simulate_batch(d["o"], sarg, d["M"], pts, d["o_est"], 0, cnt)
-    dt = time.perf_counter() - t
-    steps = int(r["job_steps"].sum())
-    return {"value": steps / dt, "unit": "job-decode-steps/s", "cores": 1, "kind": "oracle",
-            "sample": f"instances 0..{cnt - 1} of the workload at all {len(pts)} sweep points, "
-                      f"{steps} job-steps in {dt:.1f} s, literal round-by-round stepping in C (-O2)"}
+    steps1 = run(0, cnt1)
+    dt1 = time.perf_counter() - t
+    threads = max(1, min(threads, avail))
+    per = int(max(1, min(avail // threads, half / per_inst)))
+    cuts = [(j * per, (j + 1) * per) for j in range(threads)]
+    with ThreadPoolExecutor(threads) as ex:
+        t = time.perf_counter()
+        stepsN = sum(ex.map(lambda c: run(*c), cuts))
+        dtN = time.perf_counter() - t
+    return {"value": stepsN / dtN, "unit": "job-decode-steps/s", "cores": threads, "kind": "oracle",
+            "value_1core": steps1 / dt1,
+            "sample": f"literal round-by-round stepping in C (-O2) at all {len(pts)} sweep points: instances "
+                      f"0..{threads * per - 1} of the workload in {threads} disjoint ranges on {threads} threads, "
+                      f"{stepsN} job-steps in {dtN:.1f} s; one core alone: instances 0..{cnt1 - 1}, "
+                      f"{steps1} job-steps in {dt1:.1f} s"}
 
 
 def main():
@@ -100,7 +124,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the largest sweep)")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time of the oracle baseline; 0 skips it")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="wall time of the oracle baseline (half on one core, half on all threads); 0 skips it")
     ap.add_argument("--threads", type=int, default=min(16, os.cpu_count() or 1))
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies: a kernel of known traffic "
@@ -159,6 +183,8 @@ def main():
     alg_bytes = n_eval * (w.n_jobs * bytes_per_job + 25)
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
     fused_bytes = w.n_instances * w.n_jobs * bytes_per_job + n_eval * 25
+    kv = measured_counters(w.name)
+    valu = int(kv["valu_wave_instructions_per_launch"]) if "valu_wave_instructions_per_launch" in kv else None
     res = {
         "metric": "simulated job-decode-steps/sec on 1 MI355X + % of HBM roofline",
         "value": job_steps / (ms_step * 1e-3),
@@ -175,10 +201,14 @@ def main():
                      "algorithmic_bytes_per_launch": alg_bytes,
                      # the fused kernel reads an instance once per launch, not once per point
                      "fused_bytes_per_launch": fused_bytes,
-                     "achieved_fused": fused_bytes / (kern_ms * 1e-3) / 1e9},
+                     "achieved_fused": fused_bytes / (kern_ms * 1e-3) / 1e9,
+                     # issue slots: a vector instruction holds one of 1024 SIMDs for 4 cycles at 2.4 GHz;
+                     # the instruction count is rocprofv3's SQ_INSTS_VALU of the same kernel (null when the
+                     # sources have changed since it was taken)
+                     "valu_utilisation": None if valu is None else valu * 4 / (1024 * 2.4e9 * kern_ms * 1e-3)},
     }
     if args.cpu_seconds > 0:
-        res["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
+        res["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds, args.threads)
     print(json.dumps(res))
 
 
