@@ -86,6 +86,10 @@ def lib():
         _lib.kvo_opt_perm.argtypes = [i64, p32, i64, i64, p64]
         _lib.kvo_opt_exact.restype = C.c_int
         _lib.kvo_opt_exact.argtypes = [i64, p32, i64, i64, p64]
+        _lib.kvo_area_lb.restype = C.c_int
+        _lib.kvo_area_lb.argtypes = [i64, p32, p32, i64, p64]
+        _lib.kvo_upper_gba.restype = C.c_int
+        _lib.kvo_upper_gba.argtypes = [i64, p32, p32, i64, i64, i64, p64]
     return _lib
 
 
@@ -272,3 +276,24 @@ def opt_exact(o, s: int, M: int) -> int:
     best = C.c_int64()
     _check(lib().kvo_opt_exact(len(o), _p32(o), s, M, C.byref(best)))
     return best.value
+
+
+def area_lb(o, s) -> int:
+    """Numerator of the area lower bound on OPT: sum_j (n - j + 1) * Area_j, areas ascending
+    (proof of the area-based lower bound for OPT).  OPT >= area_lb / M."""
+    o = _i32(o)
+    s_arr = None if np.isscalar(s) else _i32(s)
+    num = C.c_int64()
+    _check(lib().kvo_area_lb(len(o), _p32(o), _p32(s_arr), int(s) if np.isscalar(s) else 0,
+                             C.byref(num)))
+    return num.value
+
+
+def upper_gba(o, s, M: int, tau0: int) -> int:
+    """UpperGBA = sum_p (n_p * S_p + Q_p) on the ladder tau0 * 2^p (analysis of GBA, Step 3)."""
+    o = _i32(o)
+    s_arr = None if np.isscalar(s) else _i32(s)
+    up = C.c_int64()
+    _check(lib().kvo_upper_gba(len(o), _p32(o), _p32(s_arr), int(s) if np.isscalar(s) else 0,
+                               M, tau0, C.byref(up)))
+    return up.value

@@ -723,3 +723,101 @@ int kvo_opt_exact(int64_t n, const int32_t *o, int64_t s, int64_t M,
     *best_flow = d.best;
     return KVO_OK;
 }
+
+/* ------------------------------------------------------------------------ */
+/* Bounds of the analysis of GBA (Section "Analysis of GBA", Steps 1 and 3)   */
+/* ------------------------------------------------------------------------ */
+
+static int cmp_i64(const void *a, const void *b)
+{
+    int64_t x = *(const int64_t *)a, y = *(const int64_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * Numerator of the memory-time area lower bound on OPT (proof of the
+ * area-based lower bound for OPT, first display): with the jobs numbered by
+ * non-decreasing area,
+ *     OPT >= (1 / M) * sum_{j = 1..n} (n - j + 1) * Area(o_j, s_j),
+ * because the first i completions of any schedule have consumed at least the
+ * i smallest areas and a round offers M units.  Returns the sum; the caller
+ * divides by M.  Per-job prompts enter through each job's own area.
+ */
+int kvo_area_lb(int64_t n, const int32_t *o, const int32_t *s, int64_t s_scalar,
+                int64_t *numerator)
+{
+    int64_t *a, j;
+    __int128 sum = 0;
+    if (n < 1)
+        return KVO_EINVAL;
+    a = (int64_t *)malloc((size_t)n * sizeof(int64_t));
+    if (!a)
+        return KVO_ENOMEM;
+    for (j = 0; j < n; j++) {
+        int64_t sj = s ? s[j] : s_scalar;
+        if (o[j] < 1 || sj < 0) {
+            free(a);
+            return KVO_EINVAL;
+        }
+        a[j] = kvo_area(o[j], sj);
+    }
+    qsort(a, (size_t)n, sizeof(int64_t), cmp_i64);
+    for (j = 1; j <= n; j++)
+        sum += (__int128)(n - j + 1) * a[j - 1];
+    free(a);
+    if (sum > (__int128)INT64_MAX)
+        return KVO_EINVAL;
+    *numerator = (int64_t)sum;
+    return KVO_OK;
+}
+
+/*
+ * The upper bound on the flow time of GBA from Step 3 of its analysis, on the
+ * ladder tau_p = tau0 * 2^p with true lengths as classes:
+ *     Q_p = n_p * tau_p + sum_{i < n_p} floor(i * tau_p / k_p)      (ladder term)
+ *     S_p = sum_{q < p} (floor(n_q * tau_q / k_q) + tau_q)          (class-prefix term)
+ *     UpperGBA = sum_p (n_p * S_p + Q_p)
+ * over the classes p = 0 .. the last class that has a job; k_p is the largest
+ * memory-feasible parallelism for tau_p and the largest prompt of the class
+ * (never below 1; an empty class takes the prompt 0, its k_p multiplies
+ * n_q = 0 and does not matter).
+ */
+int kvo_upper_gba(int64_t n, const int32_t *o, const int32_t *s, int64_t s_scalar,
+                  int64_t M, int64_t tau0, int64_t *upper)
+{
+    enum { MAXC = 64 };
+    int64_t cnt[MAXC], smax[MAXC], tau[MAXC], kk[MAXC];
+    int64_t j, p, last = 0, total = 0;
+    if (n < 1 || tau0 < 1 || M < 1)
+        return KVO_EINVAL;
+    for (p = 0; p < MAXC; p++)
+        cnt[p] = smax[p] = 0;
+    for (j = 0; j < n; j++) {
+        int64_t sj = s ? s[j] : s_scalar, t = tau0;
+        if (o[j] < 1 || sj < 0)
+            return KVO_EINVAL;
+        if (sj + o[j] > M)
+            return KVO_EJOB_INFEASIBLE;
+        for (p = 0; t < o[j]; p++)
+            t *= 2;
+        cnt[p]++;
+        if (sj > smax[p])
+            smax[p] = sj;
+        if (p > last)
+            last = p;
+    }
+    for (p = 0; p <= last; p++) {
+        tau[p] = tau0 << p;
+        kk[p] = phase_parallelism(KVO_SPS, tau[p], smax[p], M, 0);
+    }
+    for (p = 0; p <= last; p++) {
+        int64_t Q = cnt[p] * tau[p], S = 0, i, q;
+        for (i = 0; i < cnt[p]; i++)
+            Q += (i * tau[p]) / kk[p];
+        for (q = 0; q < p; q++)
+            S += (cnt[q] * tau[q]) / kk[q] + tau[q];
+        total += cnt[p] * S + Q;
+    }
+    *upper = total;
+    return KVO_OK;
+}

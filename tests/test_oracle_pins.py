@@ -519,3 +519,63 @@ def test_gba_ratio_theorem_on_the_papers_ladder(num, den, gamma_num, gamma_den):
         # the parallelism never grows with the slice (used in the GSA analysis)
         ks = [max(1, O.kstar(int(t), s, M)) for t in lad]
         assert all(ks[i] >= ks[i + 1] for i in range(len(ks) - 1))
+
+
+# --------------------------------------------------------------------------
+# Bounds of the analysis of GBA: UpperGBA (Step 3) and the area lower bound
+# on OPT (Step 1, first display of its proof)
+# --------------------------------------------------------------------------
+def test_upper_gba_printed_values_and_hand_example():
+    # a single class whose slice equals the common length: the ladder term IS the SPS flow
+    # time, so the bound equals the two printed flow times
+    g = GOLD["example1_sps"]
+    assert O.upper_gba([g["o"]] * g["n"], g["s"], g["M"], g["tau"]) == g["flow"]
+    u = GOLD["uniform_gba"]
+    assert O.upper_gba([u["o"]] * u["n"], u["s"], u["M"], 16) == u["flow"]
+    # on the ladder 1, 2, 4, 8, 16 the four empty classes in front still cost their slices
+    # in the class-prefix term: S_4 = 1 + 2 + 4 + 8
+    assert O.upper_gba([u["o"]] * u["n"], u["s"], u["M"], 1) == u["flow"] + u["n"] * 15
+    # by hand: o = 1, 1, 3, 4, s = 0, M = 4, slices 1, 2, 4 -> n = 2, 0, 2, k = 4, 2, 1
+    #   Q_0 = 2*1 + 0 + 0 = 2, S_0 = 0;  S_1 = floor(2*1/4) + 1 = 1
+    #   S_2 = S_1 + floor(0*2/2) + 2 = 3,  Q_2 = 2*4 + 0 + floor(4/1) = 12
+    assert O.upper_gba([1, 1, 3, 4], 0, 4, 1) == (0 + 2) + (2 * 3 + 12) == 20
+    assert O.gba_simulate([1, 1, 3, 4], 0, 4, 1, O.SPS)["flow"] == 1 + 1 + 4 + 9
+    # the class-prefix term counts n_q, not n_q - 1: o = 1,1,1,1,2, s = 0, M = 2 -> k = 2, 1
+    #   Q_0 = 4 + (0+0+1+1) = 6,  S_1 = floor(4*1/2) + 1 = 3,  Q_1 = 2
+    assert O.upper_gba([1, 1, 1, 1, 2], 0, 2, 1) == 6 + (3 + 2) == 11
+    # unit jobs that all fit at once: bound = flow = n
+    assert O.upper_gba([1] * 50, 0, 64, 1) == 50 == O.gba_simulate([1] * 50, 0, 64, 1, O.SPS)["flow"]
+
+
+def test_upper_gba_bounds_the_stepped_flow():
+    # Lemma "GBA Upper Bound via Packing Efficiency": GBA <= UpperGBA, with common and with
+    # per-job prompts (largest prompt of the class in k_p), order of the jobs irrelevant
+    rng = np.random.default_rng(21)
+    for _ in range(80):
+        n = int(rng.integers(1, 150))
+        o = np.minimum(rng.geometric(1 / 25, n), 400).astype(np.int32)
+        s = rng.integers(0, 50, n).astype(np.int32) if rng.random() < 0.5 else int(rng.integers(0, 50))
+        M = int(rng.integers(500, 4000))
+        tau0 = int(rng.choice([1, 2, 3, 4, 7, 16]))
+        up = O.upper_gba(o, s, M, tau0)
+        assert O.gba_simulate(o, s, M, tau0, O.SPS)["flow"] <= up
+        perm = rng.permutation(n)
+        assert O.upper_gba(o[perm], s if np.isscalar(s) else s[perm], M, tau0) == up
+
+
+def test_area_lower_bound():
+    # by hand: areas 3*2 + 6 = 12 and 1*2 + 1 = 3, smallest first: 2*3 + 1*12
+    assert O.area_lb([3, 1], 2) == 18 == O.area_lb([1, 3], 2)
+    assert O.area_lb([7], 5) == 5 * 7 + 28
+    # Lemma "Area-Based Lower Bound on Optimal Flow Time", identical jobs: n(n+1)/2 * Area
+    assert O.area_lb([6] * 9, 4) == 45 * (4 * 6 + 21)
+    # per-job prompts: ordered by area, not by length (o=2,s=10 -> 23; o=4,s=0 -> 10)
+    assert O.area_lb([2, 4], np.array([10, 0], np.int32)) == 2 * 10 + 23
+    rng = np.random.default_rng(5)
+    for _ in range(25):     # never above the true optimum found by exhaustive search
+        n = int(rng.integers(1, 6))
+        o = rng.integers(1, 9, n).astype(np.int32)
+        s = int(rng.integers(0, 4))
+        M = int(rng.integers(s + 8, 30))
+        assert O.area_lb(o, s) <= O.opt_exact(o, s, M) * M
+        assert O.area_lb(o, s) == _area_lb_times_M(o.tolist(), s)
