@@ -118,6 +118,94 @@ def cpu_baseline(w, target_seconds, threads):
                       f"{steps1} job-steps in {dt1:.1f} s"}
 
 
+def timed(torch, steps, warmup, call):
+    """ms per step by wall clock around `steps` calls, and by events on the calls' stream."""
+    for _ in range(warmup):
+        call()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        call()
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall * 1e3 / steps, sum(a.elapsed_time(b) for a, b in ev) / steps
+
+
+def bench_bounds(args, torch, K, W):
+    """The evaluators that frame the flow time: kvs_flow_bounds on the workload's instances at the
+    initial slices 1..128, or kvs_opt_perm on 4096 instances of the 8-job workload's shape."""
+    import oracle as O
+    import numpy as np
+    if args.path == "bounds":
+        w = W.WORKLOADS[args.config]
+        tau0 = [1, 2, 4, 8, 16, 32, 64, 128]
+        o, s, _ = load_workload(w, torch, args.threads)
+        sarg = s if s is not None else w.s_scalar
+        out = K.flow_bounds(o, sarg, w.M, tau0)
+        ms_step, kern_ms = timed(torch, args.steps, args.warmup,
+                                 lambda: K.flow_bounds(o, sarg, w.M, tau0, out=out))
+        assert int(out["upper_gba"].min().item()) > 0 and int(out["area_lb_num"].min().item()) > 0
+        n_eval = w.n_instances * (len(tau0) + 1)
+        alg_bytes = w.n_instances * (w.n_jobs * 4 * (1 + (s is not None)) + 8 * (len(tau0) + 1))
+        res = {"metric": "bounds (UpperGBA per initial slice + area lower bound) per second on 1 MI355X",
+               "value": n_eval / (ms_step * 1e-3), "unit": "bounds/s",
+               "config": {"workload": w.name, "n_instances": w.n_instances, "n_jobs": w.n_jobs, "M": w.M,
+                          "initial_slices": len(tau0)},
+               "kernel": "kvs_bounds_kernel"}
+        cpu = None
+        if args.cpu_seconds > 0:
+            d = W.generate(w, 0, 64)
+            sh = d["s"] if d["s"] is not None else None
+            t0, cnt = time.perf_counter(), 0
+            while time.perf_counter() - t0 < args.cpu_seconds / 2 and cnt < 64:
+                si = sh[cnt] if sh is not None else d["s_scalar"]
+                for t in tau0:
+                    O.upper_gba(d["o"][cnt], si, w.M, t)
+                O.area_lb(d["o"][cnt], si)
+                cnt += 1
+            dt = time.perf_counter() - t0
+            cpu = {"value": cnt * (len(tau0) + 1) / dt, "unit": "bounds/s", "cores": 1, "kind": "oracle",
+                   "sample": f"instances 0..{cnt - 1} of the workload, {len(tau0)} slices + area bound each, {dt:.1f} s"}
+    else:
+        w = W.WORKLOADS[1]
+        I = 4096
+        rng = np.random.default_rng(0)
+        oh = rng.integers(1, 33, (I, w.n_jobs)).astype(np.int32)       # config 1's shape: 8 jobs, o in 1..32
+        o = torch.from_numpy(oh).cuda()
+        out = K.opt_perm(o, w.s_scalar, w.M)
+        ms_step, kern_ms = timed(torch, args.steps, args.warmup,
+                                 lambda: K.opt_perm(o, w.s_scalar, w.M, out=out))
+        orders = 40320 * I
+        alg_bytes = I * (w.n_jobs * 4 + 8)
+        res = {"metric": "list schedules (orders of an 8-job instance) evaluated per second on 1 MI355X",
+               "value": orders / (ms_step * 1e-3), "unit": "orders/s",
+               "config": {"workload": "cfg1_shape_x4096", "n_instances": I, "n_jobs": w.n_jobs, "M": w.M,
+                          "s": w.s_scalar, "orders_per_instance": 40320},
+               "kernel": "kvs_opt_perm_kernel"}
+        cpu = None
+        if args.cpu_seconds > 0:
+            t0, cnt = time.perf_counter(), 0
+            while time.perf_counter() - t0 < args.cpu_seconds / 2 and cnt < I:
+                assert O.opt_perm(oh[cnt], w.s_scalar, w.M) == int(out[cnt].item())
+                cnt += 1
+            dt = time.perf_counter() - t0
+            cpu = {"value": cnt * 40320 / dt, "unit": "orders/s", "cores": 1, "kind": "oracle",
+                   "sample": f"instances 0..{cnt - 1} (all orders each, results equal to the GPU's), {dt:.1f} s"}
+    achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
+    res.update({"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64",
+                "data": "synthetic",
+                "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": res.pop("kernel"),
+                             "kernel_ms": kern_ms, "algorithmic_bytes_per_launch": alg_bytes}})
+    if cpu:
+        res["cpu_baseline"] = cpu
+    print(json.dumps(res))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -126,6 +214,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the largest sweep)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="wall time of the oracle baseline (half on one core, half on all threads); 0 skips it")
     ap.add_argument("--threads", type=int, default=min(16, os.cpu_count() or 1))
+    ap.add_argument("--path", choices=["sweep", "bounds", "opt_perm"], default="sweep",
+                    help="sweep: the schedule evaluation (default); bounds: UpperGBA and the area lower "
+                         "bound on the same workload; opt_perm: best order of 8-job instances by brute force")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies: a kernel of known traffic "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -142,6 +233,8 @@ def main():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
     K.lib()
+    if args.path != "sweep":
+        return bench_bounds(args, torch, K, W)
     w = W.WORKLOADS[args.config]
     pts = w.sweep()
     o, s, e = load_workload(w, torch, args.threads)

@@ -183,6 +183,57 @@ int32_t kvs_paper_ladder(int64_t M, int64_t s, int32_t alpha_num, int32_t alpha_
  */
 int32_t kvs_validate(const kvs_jobs_t *jobs, void *stream);
 
+/*
+ * The two bounds between which the analysis of GBA places its flow time
+ * (Section "Analysis of GBA"), per instance, next to the schedules themselves:
+ *
+ * upper_gba (device, int64 [n_pts][n_instances]): the upper bound of Step 3
+ * (Lemma "GBA Upper Bound via Packing Efficiency") on the ladder
+ * tau_p = tau0[q] * 2^p with the true lengths as classes,
+ *     Q_p = n_p tau_p + sum_{i < n_p} floor(i tau_p / k_p)          (ladder term),
+ *     S_p = sum_{q < p} (floor(n_q tau_q / k_q) + tau_q)            (class-prefix term),
+ *     UpperGBA = sum_p (n_p S_p + Q_p),  p = 0 .. the last class with a job,
+ * k_p = max(1, k*(tau_p, s)) of eq. (max-parallelism) with s the largest prompt
+ * of the class (0 for an empty class).  Always >= the flow of kvs_gba_simulate
+ * at (tau0, SPS, k = 0, GBA) without estimates.
+ *
+ * area_lb_num (device, int64 [n_instances]): numerator of the memory-time area
+ * lower bound on OPT (Step 1, first display of the proof of Lemma "Area-Based
+ * Lower Bound for OPT"): with the jobs numbered by non-decreasing area
+ * Area(o, s) = s o + o (o + 1) / 2,
+ *     OPT >= (1 / M) sum_{j = 1..n} (n - j + 1) Area(o_j, s_j);
+ * the sum is returned, the caller divides by M.
+ *
+ * tau0: host, n_pts entries in [1, 2^30].  o_est is ignored.  Either output
+ * may be NULL (upper_gba only with n_pts == 0).  In-band errors, value -1: an
+ * invalid job (as KVS_FEASIBLE_EINVAL); upper_gba also when some class has
+ * n_p tau_p >= 2^31; area_lb_num also when n (n + 1) / 2 times the largest
+ * area reaches 2^63.  Return values as kvs_gba_simulate.
+ */
+int32_t kvs_flow_bounds(const kvs_jobs_t *jobs, const int32_t *tau0, int32_t n_pts,
+                        int64_t *upper_gba, int64_t *area_lb_num, void *stream);
+
+#define KVS_MAX_PERM_JOBS 10          /* jobs per instance of kvs_opt_perm (10! orders) */
+#define KVS_MAX_PERM_ROUNDS (1 << 20) /* largest sum of the lengths of such an instance  */
+
+/*
+ * Best list schedule over every order of the jobs, for tiny instances: a
+ * feasible schedule without kills or pauses, hence an upper bound on OPT
+ * (Section 2.1: OPT needs neither), and OPT itself on many tiny instances.
+ * For an order, the
+ * jobs are started one after the other, each at the earliest round, not before
+ * its predecessor's start, at which its whole run s + 1 .. s + o fits on top
+ * of the runs already placed in every round (eq. (Memory-Feasibility)); the
+ * flow time of the order is the sum of start + o.  best_flow (device, int64
+ * [n_instances]) receives the minimum over all n_jobs! orders, or -1 for an
+ * instance with an invalid job or with lengths that sum to more than
+ * KVS_MAX_PERM_ROUNDS.
+ *
+ * Needs a common prompt length (jobs->s == NULL, else KVS_EINVAL) and
+ * n_jobs <= KVS_MAX_PERM_JOBS (else KVS_ELIMIT); o_est is ignored.
+ */
+int32_t kvs_opt_perm(const kvs_jobs_t *jobs, int64_t *best_flow, void *stream);
+
 /* Static, human-readable text for a status code. */
 const char *kvs_strerror(int32_t status);
 

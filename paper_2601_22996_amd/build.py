@@ -6,7 +6,7 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = [os.path.join(HERE, "csrc", "kvs_kernels.hip")]
+SOURCES = [os.path.join(HERE, "csrc", "kvs_kernels.hip"), os.path.join(HERE, "csrc", "kvs_bounds.hip")]
 HEADERS = [os.path.join(HERE, "csrc", "kvs_math.h"), os.path.join(ROOT, "include", "kvsched.h")]
 LIB = os.path.join(HERE, "libkvsched.so")
 

@@ -1,0 +1,517 @@
+/*
+ * kvs_bounds.hip -- the bounds that frame a schedule's flow time, on gfx950:
+ * UpperGBA and the memory-time area lower bound on OPT (analysis of GBA,
+ * Steps 3 and 1), and the best list schedule over all orders of a tiny
+ * instance.  Paper: "Competitive Non-Clairvoyant KV-Cache Scheduling for LLM
+ * Inference" (Feng, Yang, Zhang).
+ *
+ * Entry points: kvs_flow_bounds, kvs_opt_perm (see kvsched.h).
+ */
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include "kvs_math.h"
+#include "kvsched.h"
+
+namespace {
+
+constexpr uint32_t kLenMax = 1u << 30;
+constexpr int kWave = 64;
+constexpr int kLevels = 32;     /* levels of a ladder base * 2^g that lengths <= 2^30 can reach */
+constexpr int kMaxBases = 64;   /* distinct odd parts among the initial slices of a call       */
+
+struct BJobs {
+    const int32_t *o, *s;
+    int32_t n_inst, n_jobs;
+    uint32_t s_scalar;
+    uint64_t M;
+};
+
+/* Points of one call: point q has the initial slice base[grp[q]] << shift[q]. */
+struct BPoints {
+    uint32_t base[kMaxBases];
+    uint8_t lg_base[kMaxBases];
+    uint8_t grp[KVS_MAX_POINTS];
+    uint8_t shift[KVS_MAX_POINTS];
+    int32_t n_pts, n_bases;
+};
+
+/*
+ * sum_{i = 0}^{n-1} floor(i * tau / k): the start offsets of Procedure 1 summed
+ * over a phase of n jobs (the second part of the ladder term Q_p in the analysis
+ * of GBA).  Euclid-like reduction: whole multiples of k in tau are summed in
+ * closed form, then the lattice points under the line are counted from the
+ * other axis, which swaps the roles of tau and k; O(log) steps.  Needs k >= 1
+ * and a result below 2^63 (n <= 2^14, tau < 2^31, k < 2^41 are safe).
+ */
+KVS_HD uint64_t kvs_floor_sum(uint64_t n, uint64_t k, uint64_t tau)
+{
+    uint64_t ans = 0, a = tau, m = k, b = 0;
+    for (;;) {
+        if (a >= m) {
+            ans += (n - 1u) * n / 2u * (a / m);
+            a %= m;
+        }
+        if (b >= m) {
+            ans += n * (b / m);
+            b %= m;
+        }
+        uint64_t y = a * n + b;
+        if (y < m)
+            return ans;
+        n = y / m;
+        b = y % m;
+        uint64_t t = m;
+        m = a;
+        a = t;
+    }
+}
+
+__device__ __forceinline__ uint64_t wave_sum64(uint64_t v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1)
+        v += __shfl_xor(v, d, kWave);
+    return v;
+}
+
+__device__ __forceinline__ uint64_t wave_max64(uint64_t v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        uint64_t w = __shfl_xor(v, d, kWave);
+        v = w > v ? w : v;
+    }
+    return v;
+}
+
+/*
+ * One workgroup per instance.
+ *
+ * LDS: the jobs as (o, s) pairs, later overwritten by their 64-bit areas and
+ * sorted; per wavefront one histogram of the levels of the current base.
+ *
+ * 1. load and check the jobs;
+ * 2. per distinct base: count the jobs and keep the largest prompt per level
+ *    g (smallest g with base * 2^g >= o).  The class of a job at the point
+ *    base * 2^m is max(0, g - m), so a point's class table is the level table
+ *    with the levels 0..m merged.  32 consecutive lanes take the classes of
+ *    one point: each computes k_p, Q_p and floor(n_p tau_p / k_p) + tau_p, a
+ *    prefix sum over the lanes gives S_p, a sum n_p S_p + Q_p the bound
+ *    (Step 3 of the analysis of GBA);
+ * 3. areas in place of the pairs, bitonic sort, sum of (n - j) * area_j over
+ *    the ascending sequence j = 0 .. n-1 (Step 1, proof of the lower bound).
+ */
+template <int T>
+__global__ __launch_bounds__(T) void kvs_bounds_kernel(BJobs J, BPoints P, int64_t *upper,
+                                                        int64_t *area_num)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    uint64_t *key = reinterpret_cast<uint64_t *>(lds_raw); /* n_pad entries */
+    constexpr int NW = T / kWave;
+    __shared__ uint32_t hist[NW][kLevels];
+    __shared__ uint32_t smax_lv[kLevels];
+    __shared__ uint32_t cnt_lv[kLevels];
+    __shared__ uint32_t bad;
+    __shared__ uint64_t red[NW];
+
+    const uint32_t inst = blockIdx.x, tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const uint32_t n = (uint32_t)J.n_jobs;
+    const size_t row = (size_t)inst * n;
+    uint32_t n_pad = 1;
+    while (n_pad < n)
+        n_pad <<= 1;
+
+    if (tid == 0)
+        bad = 0;
+    __syncthreads();
+
+    /* 1. load */
+    uint32_t my_bad = 0;
+    for (uint32_t i = tid; i < n; i += T) {
+        const int32_t o = J.o[row + i];
+        const int64_t s = J.s ? (int64_t)J.s[row + i] : (int64_t)J.s_scalar;
+        if (o < 1 || s < 0 || (uint32_t)o > kLenMax || s > (int64_t)kLenMax ||
+            (uint64_t)s + (uint64_t)o > J.M) {
+            my_bad = 1;
+            key[i] = 1; /* o = 1, s = 0: keeps the loops below in range */
+        } else {
+            key[i] = ((uint64_t)(uint32_t)s << 32) | (uint32_t)o;
+        }
+    }
+    if (my_bad)
+        atomicOr(&bad, 1u);
+    __syncthreads();
+    const bool invalid = bad != 0;
+
+    /* 2. class tables and UpperGBA: 32 consecutive lanes hold the 32 classes of one point */
+    if (upper && P.n_pts > 0) {
+        for (int b = 0; b < P.n_bases; b++) {
+            for (uint32_t i = tid; i < NW * kLevels; i += T)
+                (&hist[0][0])[i] = 0;
+            if (tid < kLevels)
+                smax_lv[tid] = 0;
+            __syncthreads();
+            const uint32_t base = P.base[b], lg = P.lg_base[b];
+            for (uint32_t i = tid; i < n; i += T) {
+                const uint64_t e = key[i];
+                const uint32_t o = (uint32_t)e, s = (uint32_t)(e >> 32);
+                const uint32_t g = kvs_class_index(o, base, lg);
+                atomicAdd(&hist[wave][g], 1u);
+                if (s > smax_lv[g])
+                    atomicMax(&smax_lv[g], s);
+            }
+            __syncthreads();
+            if (tid < kLevels) {
+                uint32_t c = 0;
+                for (int w = 0; w < NW; w++)
+                    c += hist[w][tid];
+                cnt_lv[tid] = c;
+            }
+            __syncthreads();
+            for (uint32_t item0 = 0; item0 < (uint32_t)P.n_pts * kLevels; item0 += T) {
+                const uint32_t item = item0 + tid;
+                const uint32_t q = item / kLevels, p = item % kLevels; /* p == lane % 32 */
+                const bool mine = q < (uint32_t)P.n_pts && P.grp[q < KVS_MAX_POINTS ? q : 0] == b;
+                const uint32_t m = mine ? P.shift[q] : 0u;
+                uint32_t np = 0, sp = 0;
+                if (mine && p == 0) {
+                    for (uint32_t g = 0; g <= m && g < kLevels; g++) {
+                        np += cnt_lv[g];
+                        sp = smax_lv[g] > sp ? smax_lv[g] : sp;
+                    }
+                } else if (mine && p + m < kLevels) {
+                    np = cnt_lv[p + m];
+                    sp = smax_lv[p + m];
+                }
+                const uint64_t tau = ((uint64_t)base << m) << p; /* < 2^62 */
+                uint64_t Q = 0, L = tau;                         /* L = floor(n tau / k) + tau */
+                uint32_t wide = 0;
+                if (np > 0) {
+                    if ((uint64_t)np * tau >= (1ull << 31)) {
+                        wide = 1;
+                    } else {
+                        uint64_t k = kvs_kstar(tau, sp, J.M);
+                        k = k < 1 ? 1 : k;
+                        Q = (uint64_t)np * tau + kvs_floor_sum(np, k, tau);
+                        L = ((uint64_t)np * tau) / k + tau;
+                    }
+                }
+                /* S_p: exclusive prefix sum of L over the 32 lanes of the point */
+                uint64_t S = L;
+#pragma unroll
+                for (int d = 1; d < kLevels; d <<= 1) {
+                    const uint64_t v = __shfl_up(S, d, kLevels);
+                    if ((int)p >= d)
+                        S += v;
+                }
+                S -= L;
+                uint64_t term = (uint64_t)np * S + Q;
+#pragma unroll
+                for (int d = kLevels / 2; d >= 1; d >>= 1) {
+                    term += __shfl_xor(term, d, kLevels);
+                    wide |= __shfl_xor(wide, d, kLevels);
+                }
+                if (mine && p == 0)
+                    upper[(size_t)q * J.n_inst + inst] = (invalid || wide) ? -1 : (int64_t)term;
+            }
+            __syncthreads();
+        }
+    }
+
+    if (!area_num)
+        return;
+
+    /* 3. areas, sorted ascending */
+    uint64_t amax = 0;
+    for (uint32_t i = tid; i < n_pad; i += T) {
+        uint64_t a = ~0ull; /* padding sorts to the end */
+        if (i < n) {
+            const uint64_t e = key[i];
+            const uint64_t o = (uint32_t)e, s = e >> 32;
+            a = s * o + o * (o + 1u) / 2u; /* Area(o, s) < 2^61 */
+            amax = a > amax ? a : amax;
+        }
+        key[i] = a;
+    }
+    amax = wave_max64(amax);
+    if (lane == 0)
+        red[wave] = amax;
+    __syncthreads();
+    amax = 0;
+    for (int w = 0; w < NW; w++)
+        amax = red[w] > amax ? red[w] : amax;
+    __syncthreads();
+
+    for (uint32_t k = 2; k <= n_pad; k <<= 1) {
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            for (uint32_t i = tid; i < n_pad / 2; i += T) {
+                const uint32_t lo = ((i & ~(j - 1u)) << 1) | (i & (j - 1u)); /* bit log2(j) clear */
+                const uint32_t hi = lo | j;
+                const uint64_t a = key[lo], b = key[hi];
+                const bool asc = (lo & k) == 0;
+                if ((a > b) == asc) {
+                    key[lo] = b;
+                    key[hi] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    uint64_t sum = 0;
+    for (uint32_t i = tid; i < n; i += T)
+        sum += (uint64_t)(n - i) * key[i];
+    sum = wave_sum64(sum);
+    if (lane == 0)
+        red[wave] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        uint64_t tot = 0;
+        for (int w = 0; w < NW; w++)
+            tot += red[w];
+        const uint64_t tri = (uint64_t)n * (n + 1u) / 2u;
+        const bool wide = __umul64hi(tri, amax) != 0 || tri * amax >= (1ull << 63);
+        area_num[inst] = (invalid || wide) ? -1 : (int64_t)tot;
+    }
+}
+
+/* ---- best list schedule over all orders ---- */
+
+constexpr int kPermT = 256;          /* threads per workgroup                  */
+constexpr uint32_t kPermPer = 32;    /* orders per thread                      */
+constexpr int kPN = KVS_MAX_PERM_JOBS;
+constexpr uint64_t kPermRounds = KVS_MAX_PERM_ROUNDS; /* largest sum of lengths of an instance */
+
+__global__ void kvs_opt_init_kernel(BJobs J, int64_t *best)
+{
+    const uint32_t inst = blockIdx.x * blockDim.x + threadIdx.x;
+    if (inst >= (uint32_t)J.n_inst)
+        return;
+    bool ok = true;
+    uint64_t total = 0;
+    for (int j = 0; j < J.n_jobs; j++) {
+        const int32_t o = J.o[(size_t)inst * J.n_jobs + j];
+        ok = ok && o >= 1 && (uint32_t)o <= kLenMax && (uint64_t)J.s_scalar + (uint64_t)o <= J.M;
+        total += ok ? (uint64_t)o : 0u;
+    }
+    best[inst] = (ok && total <= kPermRounds) ? INT64_MAX : -1;
+}
+
+/*
+ * Flow time of the list schedule for order number idx in the factorial number
+ * system (digit j picks among the n - j jobs not yet placed).  The jobs
+ * already placed all start at or before the candidate start S, so from S on
+ * the placed load only falls when one of them ends and rises by one per job
+ * and round in between: the new run fits iff it fits in its own last round
+ * and in the last round of every placed run that ends inside it.  When it
+ * does not fit because some round t is over the budget by x, every start
+ * before min(S + x, t + 1) still has round t inside the run and still over
+ * the budget, so the search jumps there instead of trying them.
+ */
+__host__ __device__ inline int64_t list_schedule_flow(uint32_t idx, int n, const uint32_t *len,
+                                                      int64_t s1, int64_t M)
+{
+    uint64_t avail = 0x9876543210ull; /* job ids not yet placed, 4 bits each */
+    int64_t S_of[kPN], E_of[kPN];     /* start and end (exclusive) of the placed runs */
+    int64_t prev = 0, flow = 0;
+#pragma unroll
+    for (int j = 0; j < kPN; j++) {
+        if (j < n) {
+            const uint32_t radix = (uint32_t)(n - j);
+            const uint32_t d = idx % radix;
+            idx /= radix;
+            const uint32_t id = (uint32_t)(avail >> (4 * d)) & 15u;
+            const uint64_t low = avail & ((1ull << (4 * d)) - 1ull);
+            avail = low | ((avail >> (4 * d + 4)) << (4 * d));
+            const int64_t o = len[id];
+            int64_t S = prev;
+            for (;;) {
+                const int64_t E = S + o;
+                int64_t jump = 0;
+                /* rounds to test: E - 1 and E_i - 1 for placed runs with S < E_i < E */
+#pragma unroll
+                for (int c = 0; c <= kPN; c++) {
+                    int64_t t;
+                    if (c == kPN)
+                        t = E - 1;
+                    else if (c < j && E_of[c] > S && E_of[c] < E)
+                        t = E_of[c] - 1;
+                    else
+                        continue;
+                    int64_t occ = s1 + (t - S);
+#pragma unroll
+                    for (int i = 0; i < kPN; i++)
+                        if (i < j && E_of[i] > t) /* started at or before S <= t */
+                            occ += s1 + (t - S_of[i]);
+                    if (occ > M) {
+                        const int64_t by = occ - M < t + 1 - S ? occ - M : t + 1 - S;
+                        jump = by > jump ? by : jump;
+                    }
+                }
+                if (jump == 0)
+                    break;
+                S += jump;
+            }
+            S_of[j] = S;
+            E_of[j] = S + o;
+            prev = S;
+            flow += S + o;
+        }
+    }
+    return flow;
+}
+
+/*
+ * Workgroup (instance, chunk): every thread evaluates kPermPer orders and the
+ * minimum goes to best[instance] with one atomic per wavefront.
+ */
+__global__ __launch_bounds__(kPermT) void kvs_opt_perm_kernel(BJobs J, int64_t *best,
+                                                               uint32_t n_orders, uint32_t chunks)
+{
+    const uint32_t inst = blockIdx.x / chunks, chunk = blockIdx.x % chunks;
+    const int n = J.n_jobs;
+    __shared__ uint32_t len[kPN];
+    if (threadIdx.x < (uint32_t)n)
+        len[threadIdx.x] = (uint32_t)J.o[(size_t)inst * n + threadIdx.x];
+    __syncthreads();
+    if (best[inst] < 0) /* invalid or too long: reported by the first kernel */
+        return;
+    const int64_t s1 = (int64_t)J.s_scalar + 1, M = (int64_t)J.M;
+
+    int64_t mine = INT64_MAX;
+    const uint32_t first = (chunk * kPermT + threadIdx.x) * kPermPer;
+    for (uint32_t c = 0; c < kPermPer && first + c < n_orders; c++) {
+        const int64_t flow = list_schedule_flow(first + c, n, len, s1, M);
+        mine = flow < mine ? flow : mine;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const int64_t w = __shfl_xor(mine, d, kWave);
+        mine = w < mine ? w : mine;
+    }
+    if (threadIdx.x % kWave == 0 && mine != INT64_MAX)
+        atomicMin(reinterpret_cast<long long *>(best + inst), (long long)mine);
+}
+
+int32_t check_bound_jobs(const kvs_jobs_t *jobs)
+{
+    if (!jobs || jobs->n_instances < 0 || jobs->n_jobs < 1)
+        return KVS_EINVAL;
+    if (jobs->n_instances > 0 && !jobs->o)
+        return KVS_EINVAL;
+    if (jobs->M < 1 || jobs->M >= (1ll << 40))
+        return KVS_EINVAL;
+    if (!jobs->s && (jobs->s_scalar < 0 || (uint32_t)jobs->s_scalar > kLenMax))
+        return KVS_EINVAL;
+    return KVS_OK;
+}
+
+BJobs to_bjobs(const kvs_jobs_t *jobs)
+{
+    BJobs J;
+    J.o = jobs->o;
+    J.s = jobs->s;
+    J.n_inst = jobs->n_instances;
+    J.n_jobs = jobs->n_jobs;
+    J.s_scalar = jobs->s ? 0u : (uint32_t)jobs->s_scalar;
+    J.M = (uint64_t)jobs->M;
+    return J;
+}
+
+} // namespace
+
+extern "C" {
+
+int32_t kvs_flow_bounds(const kvs_jobs_t *jobs, const int32_t *tau0, int32_t n_pts,
+                        int64_t *upper_gba, int64_t *area_lb_num, void *stream)
+{
+    int32_t rc = check_bound_jobs(jobs);
+    if (rc != KVS_OK)
+        return rc;
+    if (n_pts < 0 || (n_pts > 0 && (!tau0 || !upper_gba)))
+        return KVS_EINVAL;
+    if (jobs->n_jobs > KVS_MAX_JOBS || n_pts > KVS_MAX_POINTS)
+        return KVS_ELIMIT;
+    BPoints P;
+    memset(&P, 0, sizeof(P));
+    P.n_pts = n_pts;
+    for (int32_t q = 0; q < n_pts; q++) {
+        if (tau0[q] < 1 || (uint32_t)tau0[q] > kLenMax)
+            return KVS_EINVAL;
+        const uint32_t m = (uint32_t)__builtin_ctz((uint32_t)tau0[q]);
+        const uint32_t base = (uint32_t)tau0[q] >> m;
+        int b = 0;
+        while (b < P.n_bases && P.base[b] != base)
+            b++;
+        if (b == P.n_bases) {
+            P.base[b] = base;
+            P.lg_base[b] = (uint8_t)kvs_ilog2_floor(base);
+            P.n_bases++;
+        }
+        P.grp[q] = (uint8_t)b;
+        P.shift[q] = (uint8_t)m;
+    }
+    if (jobs->n_instances == 0 || (n_pts == 0 && !area_lb_num))
+        return KVS_OK;
+    uint32_t n_pad = 1;
+    while (n_pad < (uint32_t)jobs->n_jobs)
+        n_pad <<= 1;
+    const size_t lds = sizeof(uint64_t) * n_pad;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    auto launch = [&](auto kern, int threads) -> int32_t {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return KVS_EHIP;
+        hipLaunchKernelGGL(kern, dim3((uint32_t)jobs->n_instances), dim3(threads), lds, st,
+                           to_bjobs(jobs), P, n_pts > 0 ? upper_gba : nullptr, area_lb_num);
+        return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
+    };
+    return jobs->n_jobs > 2048 ? launch(kvs_bounds_kernel<1024>, 1024)
+                               : launch(kvs_bounds_kernel<256>, 256);
+}
+
+int32_t kvs_opt_perm(const kvs_jobs_t *jobs, int64_t *best_flow, void *stream)
+{
+    int32_t rc = check_bound_jobs(jobs);
+    if (rc != KVS_OK)
+        return rc;
+    if (jobs->s)
+        return KVS_EINVAL;
+    if (jobs->n_jobs > KVS_MAX_PERM_JOBS)
+        return KVS_ELIMIT;
+    if (jobs->n_instances == 0)
+        return KVS_OK;
+    if (!best_flow)
+        return KVS_EINVAL;
+    uint32_t n_orders = 1;
+    for (int j = 2; j <= jobs->n_jobs; j++)
+        n_orders *= (uint32_t)j;
+    const uint32_t per_wg = kPermT * kPermPer;
+    const uint32_t chunks = (n_orders + per_wg - 1) / per_wg;
+    if ((uint64_t)chunks * (uint64_t)jobs->n_instances > 0x7fffffffull)
+        return KVS_ELIMIT;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const BJobs J = to_bjobs(jobs);
+    hipLaunchKernelGGL(kvs_opt_init_kernel, dim3((uint32_t)(jobs->n_instances + 255) / 256), dim3(256),
+                       0, st, J, best_flow);
+    hipLaunchKernelGGL(kvs_opt_perm_kernel, dim3(chunks * (uint32_t)jobs->n_instances), dim3(kPermT),
+                       0, st, J, best_flow, n_orders, chunks);
+    return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
+}
+
+/* Host-side access to the kernels' arithmetic, for tests without a GPU. */
+uint64_t kvs_host_floor_sum(uint64_t n, uint64_t k, uint64_t tau) { return kvs_floor_sum(n, k, tau); }
+
+int64_t kvs_host_list_schedule_flow(uint32_t order, int32_t n, const int32_t *o, int64_t s, int64_t M)
+{
+    uint32_t len[kPN] = {0};
+    if (n < 1 || n > kPN)
+        return -1;
+    for (int j = 0; j < n; j++)
+        len[j] = (uint32_t)o[j];
+    return list_schedule_flow(order, n, len, s + 1, M);
+}
+
+} // extern "C"

@@ -65,6 +65,10 @@ def lib():
         L.kvs_paper_ladder.argtypes = [C.c_int64, C.c_int64, i32, i32, C.POINTER(i32), C.POINTER(i32)]
         L.kvs_validate.restype = i32
         L.kvs_validate.argtypes = [C.POINTER(_Jobs), vp]
+        L.kvs_flow_bounds.restype = i32
+        L.kvs_flow_bounds.argtypes = [C.POINTER(_Jobs), C.POINTER(i32), i32, vp, vp, vp]
+        L.kvs_opt_perm.restype = i32
+        L.kvs_opt_perm.argtypes = [C.POINTER(_Jobs), vp, vp]
         L.kvs_strerror.restype = C.c_char_p
         L.kvs_strerror.argtypes = [i32]
         L.kvs_version.restype = i32
@@ -74,6 +78,10 @@ def lib():
         L.kvs_host_div.argtypes = [C.c_uint32, C.c_uint32]
         L.kvs_host_kstar.restype = C.c_uint64
         L.kvs_host_kstar.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
+        L.kvs_host_floor_sum.restype = C.c_uint64
+        L.kvs_host_floor_sum.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
+        L.kvs_host_list_schedule_flow.restype = C.c_int64
+        L.kvs_host_list_schedule_flow.argtypes = [C.c_uint32, i32, C.POINTER(i32), C.c_int64, C.c_int64]
         _lib = L
     return _lib
 
@@ -189,6 +197,33 @@ def ladder_simulate(o: torch.Tensor, s, M: int, ladders, points, o_est: Optional
                                      mode.ctypes.data_as(p32), P, out["peak"].data_ptr(),
                                      out["feasible"].data_ptr(), out["flow"].data_ptr(),
                                      out["job_steps"].data_ptr(), _stream(stream)))
+    return out
+
+
+def flow_bounds(o: torch.Tensor, s, M: int, tau0: Sequence[int], area: bool = True,
+                out: Optional[dict] = None, stream=None) -> dict:
+    """kvs_flow_bounds.  Returns device tensors upper_gba [len(tau0)][n_instances] and (if
+    `area`) area_lb_num [n_instances]; valid after the stream is synchronised."""
+    P, I = len(tau0), o.shape[0]
+    if out is None:
+        out = dict(upper_gba=torch.empty((P, I), dtype=torch.int64, device=o.device))
+        if area:
+            out["area_lb_num"] = torch.empty((I,), dtype=torch.int64, device=o.device)
+    arr = (C.c_int32 * max(P, 1))(*map(int, tau0))
+    jobs = _jobs(o, s, M, None)
+    a = out.get("area_lb_num")
+    _check(lib().kvs_flow_bounds(C.byref(jobs), arr, P, out["upper_gba"].data_ptr(),
+                                 a.data_ptr() if a is not None else None, _stream(stream)))
+    return out
+
+
+def opt_perm(o: torch.Tensor, s: int, M: int, out: Optional[torch.Tensor] = None,
+             stream=None) -> torch.Tensor:
+    """kvs_opt_perm.  Returns the device tensor best_flow [n_instances]."""
+    if out is None:
+        out = torch.empty((o.shape[0],), dtype=torch.int64, device=o.device)
+    jobs = _jobs(o, int(s), M, None)
+    _check(lib().kvs_opt_perm(C.byref(jobs), out.data_ptr(), _stream(stream)))
     return out
 
 

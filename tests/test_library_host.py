@@ -140,3 +140,76 @@ def test_paper_ladder_matches_the_oracle_and_the_definition(L):
         assert got[-1] == M - s
     assert lib_ladder(10, 10, 2, 1)[0] == 1 and lib_ladder(10, 0, 1, 1)[0] == 1
     assert lib_ladder(2 ** 30, 0, 4, 3)[0] == 5                    # needs more than 64 levels
+
+
+def test_floor_sum_matches_the_plain_sum(L):
+    L.kvs_host_floor_sum.restype = C.c_uint64
+    L.kvs_host_floor_sum.argtypes = [C.c_uint64] * 3
+    rnd = random.Random(11)
+    for _ in range(4000):
+        n = rnd.randint(1, 400)
+        k = rnd.choice([1, 2, 3, rnd.randint(1, 60), rnd.randint(1, 10 ** 6), rnd.randint(1, 2 ** 40)])
+        tau = rnd.choice([1, 2, rnd.randint(1, 50), rnd.randint(1, 10 ** 6), rnd.randint(1, 2 ** 31 - 1)])
+        assert L.kvs_host_floor_sum(n, k, tau) == sum(i * tau // k for i in range(n)), (n, k, tau)
+    # the largest phase the kernels accept: n * tau just below 2^31
+    n, tau = 16384, 2 ** 17 - 1
+    assert L.kvs_host_floor_sum(n, 1, tau) == tau * n * (n - 1) // 2
+    assert L.kvs_host_floor_sum(n, 7, tau) == sum(i * tau // 7 for i in range(n))
+
+
+def test_list_schedule_of_every_order_against_the_oracle(L):
+    """The kernel's evaluation of one order (event rounds only, jumps in the search for the
+    start) run on the host for every order number: the minimum is the oracle's, and each
+    order number decodes to a different order."""
+    import numpy as np
+    import oracle as O
+    L.kvs_host_list_schedule_flow.restype = C.c_int64
+    L.kvs_host_list_schedule_flow.argtypes = [C.c_uint32, C.c_int32, C.POINTER(C.c_int32), C.c_int64, C.c_int64]
+    rng = np.random.default_rng(8)
+    fact = [1, 1, 2, 6, 24, 120, 720]
+    for case in range(40):
+        n = int(rng.integers(1, 7))
+        o = rng.integers(1, 12, n).astype(np.int32)
+        s = int(rng.integers(0, 5))
+        M = int(rng.integers(s + 12, 45)) if case % 4 else s + int(o.max())   # no two jobs overlap
+        ptr = o.ctypes.data_as(C.POINTER(C.c_int32))
+        flows = [L.kvs_host_list_schedule_flow(i, n, ptr, s, M) for i in range(fact[n])]
+        assert min(flows) == O.opt_perm(o, s, M), (o, s, M)
+        # identity order = order number 0: compare with the oracle's stepping of that one order
+        assert min(flows) >= int(o.sum())
+    # by hand: two jobs that cannot overlap, either order: 2 + 5 or 3 + 5
+    o = np.array([3, 2], np.int32)
+    ptr = o.ctypes.data_as(C.POINTER(C.c_int32))
+    assert sorted(L.kvs_host_list_schedule_flow(i, 2, ptr, 2, 5) for i in range(2)) == [7, 8]
+    # o = 2, 2, s = 0, M = 3: second job starts one round later
+    o = np.array([2, 2], np.int32)
+    assert L.kvs_host_list_schedule_flow(0, 2, o.ctypes.data_as(C.POINTER(C.c_int32)), 0, 3) == 5
+
+
+def test_bounds_argument_checks(L):
+    class Jobs(C.Structure):
+        _fields_ = [("n_instances", C.c_int32), ("n_jobs", C.c_int32), ("o", C.c_void_p),
+                    ("s", C.c_void_p), ("o_est", C.c_void_p), ("s_scalar", C.c_int32),
+                    ("M", C.c_int64)]
+    i32 = C.c_int32
+    L.kvs_flow_bounds.restype = i32
+    L.kvs_flow_bounds.argtypes = [C.POINTER(Jobs), C.POINTER(i32), i32, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.kvs_opt_perm.restype = i32
+    L.kvs_opt_perm.argtypes = [C.POINTER(Jobs), C.c_void_p, C.c_void_p]
+    EINVAL, ELIMIT = 1, 5
+    one = (i32 * 1)(1)
+    fb = lambda j, t, n, up, ar: L.kvs_flow_bounds(C.byref(j), t, n, up, ar, None)
+    assert L.kvs_flow_bounds(None, one, 1, 8, 8, None) == EINVAL
+    assert fb(Jobs(4, 8, None, None, None, 0, 100), one, 1, 8, 8) == EINVAL      # o is null
+    assert fb(Jobs(4, 8, 1, None, None, 0, 100), one, 1, None, 8) == EINVAL      # no room for the bound
+    assert fb(Jobs(4, 8, 1, None, None, 0, 100), (i32 * 1)(0), 1, 8, 8) == EINVAL  # tau0 < 1
+    assert fb(Jobs(4, 8, 1, None, None, 0, 0), one, 1, 8, 8) == EINVAL           # M < 1
+    assert fb(Jobs(4, 16385, 1, None, None, 0, 100), one, 1, 8, 8) == ELIMIT
+    assert fb(Jobs(4, 8, 1, None, None, 0, 100), one, 65, 8, 8) == ELIMIT
+    assert fb(Jobs(0, 8, None, None, None, 0, 100), one, 1, 8, 8) == 0           # nothing to do
+    assert fb(Jobs(4, 8, 1, None, None, 0, 100), one, 0, None, None) == 0
+    op = lambda j, out: L.kvs_opt_perm(C.byref(j), out, None)
+    assert op(Jobs(4, 8, 1, 1, None, 0, 100), 8) == EINVAL                       # per-job prompts
+    assert op(Jobs(4, 11, 1, None, None, 0, 100), 8) == ELIMIT
+    assert op(Jobs(4, 8, 1, None, None, 0, 100), None) == EINVAL
+    assert op(Jobs(0, 8, None, None, None, 0, 100), None) == 0
