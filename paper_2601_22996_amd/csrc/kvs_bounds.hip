@@ -86,11 +86,113 @@ __device__ __forceinline__ uint64_t wave_max64(uint64_t v)
     return v;
 }
 
+
+/* ---- bitonic sort of up to 16 keys per thread, in LDS ---- */
+
+constexpr int kPerThread = 16; /* keys a thread holds; a workgroup of T threads sorts up to 16 T */
+
+/* One unused word after every 16 keys: a thread that reads 16 consecutive keys and its
+ * neighbours then fall into different banks. */
+__device__ __forceinline__ uint32_t slot_of(uint32_t i) { return i + (i >> 4); }
+
+template <typename KT> __device__ __forceinline__ void order_pair(KT &a, KT &b)
+{
+    const KT lo = a < b ? a : b, hi = a < b ? b : a;
+    a = lo;
+    b = hi;
+}
+
 /*
- * One workgroup per instance.
+ * The stages j = 2^(b_low + R - 1) .. 2^b_low of the bitonic merge of block
+ * length k, fused: a thread takes the 2^R keys whose indices differ only in
+ * those R bits, runs the R stages in registers and writes them back.  The
+ * direction of a merge is the same for all keys of a thread (bit log2 k of the
+ * index); descending blocks are merged ascending on the complemented keys.
+ */
+template <typename KT, int R, int T>
+__device__ __forceinline__ void merge_stages(KT *key, uint32_t n_pad, uint32_t k, uint32_t b_low,
+                                             uint32_t tid)
+{
+    for (uint32_t g = tid; g < (n_pad >> R); g += T) {
+        const uint32_t base = ((g >> b_low) << (b_low + R)) | (g & ((1u << b_low) - 1u));
+        const KT flip = (base & k) ? ~(KT)0 : (KT)0;
+        KT v[1 << R];
+#pragma unroll
+        for (int e = 0; e < (1 << R); e++)
+            v[e] = key[slot_of(base + ((uint32_t)e << b_low))] ^ flip;
+#pragma unroll
+        for (int bit = R - 1; bit >= 0; bit--)
+#pragma unroll
+            for (int e = 0; e < (1 << R); e++)
+                if (!(e & (1 << bit)))
+                    order_pair(v[e], v[e | (1 << bit)]);
+#pragma unroll
+        for (int e = 0; e < (1 << R); e++)
+            key[slot_of(base + ((uint32_t)e << b_low))] = v[e] ^ flip;
+    }
+    __syncthreads();
+}
+
+/* Sorts key[slot_of(0 .. n_pad-1)] ascending; n_pad a power of two, 16 <= n_pad <= 16 T.
+ * Every thread of the workgroup must call it. */
+template <typename KT, int T>
+__device__ void bitonic_sort(KT *key, uint32_t n_pad, uint32_t tid)
+{
+    /* blocks of 16 consecutive keys: the merges k = 2, 4, 8, 16 entirely in registers */
+    for (uint32_t g = tid; g < n_pad / 16; g += T) {
+        const uint32_t base = g * 16;
+        KT v[16];
+#pragma unroll
+        for (int e = 0; e < 16; e++)
+            v[e] = key[slot_of(base + e)];
+#pragma unroll
+        for (int k = 2; k <= 8; k <<= 1)
+#pragma unroll
+            for (int j = k >> 1; j > 0; j >>= 1)
+#pragma unroll
+                for (int e = 0; e < 16; e++)
+                    if (!(e & j)) {
+                        if (e & k)
+                            order_pair(v[e | j], v[e]);
+                        else
+                            order_pair(v[e], v[e | j]);
+                    }
+        const KT flip = (base & 16u) ? ~(KT)0 : (KT)0;
+#pragma unroll
+        for (int j = 8; j > 0; j >>= 1)
+#pragma unroll
+            for (int e = 0; e < 16; e++)
+                if (!(e & j)) {
+                    KT a = v[e] ^ flip, b = v[e | j] ^ flip;
+                    order_pair(a, b);
+                    v[e] = a ^ flip;
+                    v[e | j] = b ^ flip;
+                }
+#pragma unroll
+        for (int e = 0; e < 16; e++)
+            key[slot_of(base + e)] = v[e];
+    }
+    __syncthreads();
+    for (uint32_t m = 5; (1u << m) <= n_pad; m++) {
+        const uint32_t k = 1u << m;
+        uint32_t b = m; /* stages of the bits b-1 .. 0 are still to do */
+        switch (m % 4) {
+        case 1: merge_stages<KT, 1, T>(key, n_pad, k, b - 1, tid); b -= 1; break;
+        case 2: merge_stages<KT, 2, T>(key, n_pad, k, b - 2, tid); b -= 2; break;
+        case 3: merge_stages<KT, 3, T>(key, n_pad, k, b - 3, tid); b -= 3; break;
+        default: break;
+        }
+        for (; b >= 4; b -= 4)
+            merge_stages<KT, 4, T>(key, n_pad, k, b - 4, tid);
+    }
+}
+
+/*
+ * One workgroup per instance (T threads, n_jobs <= 16 T).
  *
- * LDS: the jobs as (o, s) pairs, later overwritten by their 64-bit areas and
- * sorted; per wavefront one histogram of the levels of the current base.
+ * LDS: the jobs as (o, s) pairs, later overwritten by their areas (32-bit
+ * keys when the largest area allows, else 64-bit) and sorted; per wavefront
+ * one histogram of the levels of the current base.
  *
  * 1. load and check the jobs;
  * 2. per distinct base: count the jobs and keep the largest prompt per level
@@ -100,7 +202,8 @@ __device__ __forceinline__ uint64_t wave_max64(uint64_t v)
  *    one point: each computes k_p, Q_p and floor(n_p tau_p / k_p) + tau_p, a
  *    prefix sum over the lanes gives S_p, a sum n_p S_p + Q_p the bound
  *    (Step 3 of the analysis of GBA);
- * 3. areas in place of the pairs, bitonic sort, sum of (n - j) * area_j over
+ * 3. areas in place of the pairs, bitonic sort (16 keys per thread, up to four
+ *    stages per pass over LDS), sum of (n - j) * area_j over
  *    the ascending sequence j = 0 .. n-1 (Step 1, proof of the lower bound).
  */
 template <int T>
@@ -119,7 +222,7 @@ __global__ __launch_bounds__(T) void kvs_bounds_kernel(BJobs J, BPoints P, int64
     const uint32_t inst = blockIdx.x, tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const uint32_t n = (uint32_t)J.n_jobs;
     const size_t row = (size_t)inst * n;
-    uint32_t n_pad = 1;
+    uint32_t n_pad = 16;
     while (n_pad < n)
         n_pad <<= 1;
 
@@ -223,47 +326,53 @@ __global__ __launch_bounds__(T) void kvs_bounds_kernel(BJobs J, BPoints P, int64
     if (!area_num)
         return;
 
-    /* 3. areas, sorted ascending */
+    /* 3. areas, sorted ascending.  A thread takes its (at most 16) jobs out of LDS first: the
+     * sorted layout overlaps the pairs. */
+    uint64_t area[kPerThread];
     uint64_t amax = 0;
-    for (uint32_t i = tid; i < n_pad; i += T) {
-        uint64_t a = ~0ull; /* padding sorts to the end */
+#pragma unroll
+    for (int c = 0; c < kPerThread; c++) {
+        const uint32_t i = tid + (uint32_t)c * T;
+        area[c] = ~0ull; /* padding sorts to the end */
         if (i < n) {
             const uint64_t e = key[i];
             const uint64_t o = (uint32_t)e, s = e >> 32;
-            a = s * o + o * (o + 1u) / 2u; /* Area(o, s) < 2^61 */
-            amax = a > amax ? a : amax;
+            area[c] = s * o + o * (o + 1u) / 2u; /* Area(o, s) < 2^61 */
+            amax = area[c] > amax ? area[c] : amax;
         }
-        key[i] = a;
     }
     amax = wave_max64(amax);
     if (lane == 0)
         red[wave] = amax;
-    __syncthreads();
+    __syncthreads(); /* every pair has been read */
     amax = 0;
     for (int w = 0; w < NW; w++)
         amax = red[w] > amax ? red[w] : amax;
-    __syncthreads();
-
-    for (uint32_t k = 2; k <= n_pad; k <<= 1) {
-        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-            for (uint32_t i = tid; i < n_pad / 2; i += T) {
-                const uint32_t lo = ((i & ~(j - 1u)) << 1) | (i & (j - 1u)); /* bit log2(j) clear */
-                const uint32_t hi = lo | j;
-                const uint64_t a = key[lo], b = key[hi];
-                const bool asc = (lo & k) == 0;
-                if ((a > b) == asc) {
-                    key[lo] = b;
-                    key[hi] = a;
-                }
-            }
-            __syncthreads();
+    const bool narrow = amax < 0xffffffffull; /* 32-bit keys: half the LDS traffic */
+    uint32_t *key32 = reinterpret_cast<uint32_t *>(lds_raw);
+#pragma unroll
+    for (int c = 0; c < kPerThread; c++) {
+        const uint32_t i = tid + (uint32_t)c * T;
+        if (i < n_pad) {
+            if (narrow)
+                key32[slot_of(i)] = i < n ? (uint32_t)area[c] : ~0u;
+            else
+                key[slot_of(i)] = area[c];
         }
     }
-
+    __syncthreads();
     uint64_t sum = 0;
-    for (uint32_t i = tid; i < n; i += T)
-        sum += (uint64_t)(n - i) * key[i];
+    if (narrow) {
+        bitonic_sort<uint32_t, T>(key32, n_pad, tid);
+        for (uint32_t i = tid; i < n; i += T)
+            sum += (uint64_t)(n - i) * key32[slot_of(i)];
+    } else {
+        bitonic_sort<uint64_t, T>(key, n_pad, tid);
+        for (uint32_t i = tid; i < n; i += T)
+            sum += (uint64_t)(n - i) * key[slot_of(i)];
+    }
     sum = wave_sum64(sum);
+    __syncthreads();
     if (lane == 0)
         red[wave] = sum;
     __syncthreads();
@@ -455,10 +564,11 @@ int32_t kvs_flow_bounds(const kvs_jobs_t *jobs, const int32_t *tau0, int32_t n_p
     }
     if (jobs->n_instances == 0 || (n_pts == 0 && !area_lb_num))
         return KVS_OK;
-    uint32_t n_pad = 1;
+    uint32_t n_pad = 16;
     while (n_pad < (uint32_t)jobs->n_jobs)
         n_pad <<= 1;
-    const size_t lds = sizeof(uint64_t) * n_pad;
+    /* room for the (o, s) pairs and for 64-bit keys with one unused slot per 16 */
+    const size_t lds = sizeof(uint64_t) * (n_pad + n_pad / 16 + 1);
     hipStream_t st = static_cast<hipStream_t>(stream);
     auto launch = [&](auto kern, int threads) -> int32_t {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -468,8 +578,11 @@ int32_t kvs_flow_bounds(const kvs_jobs_t *jobs, const int32_t *tau0, int32_t n_p
                            to_bjobs(jobs), P, n_pts > 0 ? upper_gba : nullptr, area_lb_num);
         return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
     };
-    return jobs->n_jobs > 2048 ? launch(kvs_bounds_kernel<1024>, 1024)
-                               : launch(kvs_bounds_kernel<256>, 256);
+    /* a thread holds at most 16 keys */
+    static_assert(KVS_MAX_JOBS <= 16 * 1024, "largest instance must fit 1024 threads");
+    return n_pad > 4096   ? launch(kvs_bounds_kernel<1024>, 1024)
+           : n_pad > 1024 ? launch(kvs_bounds_kernel<256>, 256)
+                          : launch(kvs_bounds_kernel<64>, 64);
 }
 
 int32_t kvs_opt_perm(const kvs_jobs_t *jobs, int64_t *best_flow, void *stream)
