@@ -282,6 +282,8 @@ __device__ __forceinline__ unsigned long long wave_sum_u63(unsigned long long v)
 struct EntryFmt {
     uint32_t dbits;  /* duration in bits [0, dbits), done-bit at dbits, prompt above          */
     uint32_t sshift; /* where the prompt starts: dbits + 1, or dbits when no done-bit is kept */
+    uint32_t swidth; /* bits of the prompt field, 0 when no prompt is stored                  */
+    uint32_t s_add;  /* the common prompt length when none is stored, else 0                  */
     bool has_s;      /* per-job prompts are stored at all                                     */
     bool all_done;   /* every run completes: no done-bit                                      */
 };
@@ -312,13 +314,17 @@ __device__ __forceinline__ void get_entry(const uint32_t *buf, uint32_t n_cap, u
     if (PACKED) {
         d = w & ((1u << F.dbits) - 1u);
         done = F.all_done || ((w >> F.dbits) & 1u);
-        s = F.has_s ? (w >> F.sshift) : s_scalar;
+        s = __builtin_amdgcn_ubfe(w, F.sshift, F.swidth) + F.s_add; /* width 0 extracts 0 */
     } else {
         d = w & 0x7fffffffu;
         done = w >> 31;
         s = buf[n_cap + pos];
     }
 }
+
+/* An end event: one run less, and its weight w = s + 1 - start taken out: -(2^32 + w), as
+ * this constant plus the sign-extended -w. */
+constexpr unsigned long long kEndOne = 0xffffffff00000000ull;
 
 /*
  * One slab [t_s, t_s + len) of one phase variant, by one wavefront.
@@ -358,7 +364,7 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
             A0 += w;
             C0 += 1;
             if (en < (int32_t)len) {
-                atomicAdd(&ev[en], 0ull - ((1ull << 32) + (unsigned long long)(long long)w));
+                atomicAdd(&ev[en], kEndOne + (unsigned long long)(long long)(-w));
                 touched = true;
             }
         }
@@ -390,35 +396,37 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
         const uint32_t r_step = sps ? sl.tau - q_step * sc.k : 1u;
         const uint32_t wrap = sps ? 1u : sl.tau;
         uint32_t cur = 0, accS = 0, accN = 0;
-        for (uint32_t j = 0; j < blk; j++) {
-            const uint32_t r = rb + j;
-            if (r < r2) {
-                uint32_t d, s;
-                bool done;
-                get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F);
-                const uint32_t st = f - t_s; /* in [0, len) */
-                if (st != cur && accN) {
-                    atomicAdd(&ev[cur], ((unsigned long long)accN << 32) +
-                                            (unsigned long long)(long long)(int32_t)(accS - __umul24(accN, cur)));
-                    accS = 0;
-                    accN = 0;
-                }
-                cur = st;
-                accS += s + 1u;
-                accN += 1u;
-                const uint32_t en = st + d;
-                if (en < len) {
-                    const int32_t w = (int32_t)s + 1 - (int32_t)st;
-                    atomicAdd(&ev[en], 0ull - ((1ull << 32) + (unsigned long long)(long long)w));
-                }
+        const uint32_t cnt = rb < r2 ? (r2 - rb < blk ? r2 - rb : blk) : 0u;
+        for (uint32_t j = 0; j < cnt; j++) {
+            uint32_t d, s;
+            bool done;
+            get_entry<PACKED>(buf, n_cap, sl.off + rb + j, d, done, s, s_scalar, F);
+            const uint32_t st = f - t_s; /* in [0, len) */
+            if (st != cur && accN) {
+                atomicAdd(&ev[cur], ((unsigned long long)accN << 32) +
+                                        (unsigned long long)(long long)(int32_t)(accS - __umul24(accN, cur)));
+                accS = 0;
+                accN = 0;
+            }
+            cur = st;
+            accS += s + 1u;
+            accN += 1u;
+            const uint32_t en = st + d;
+            if (en < len)
+                atomicAdd(&ev[en], kEndOne + (unsigned long long)(long long)(int32_t)(st - (s + 1u)));
+            if (F.all_done) {
+                sum_st += st;
+            } else {
                 sum_st += done ? st : 0u;
                 n_done += done ? 1u : 0u;
-                rem += r_step;
-                const bool over = rem >= sc.k;
-                rem -= over ? sc.k : 0u;
-                f += q_step + (over ? wrap : 0u);
             }
+            rem += r_step;
+            const bool over = rem >= sc.k;
+            rem -= over ? sc.k : 0u;
+            f += q_step + (over ? wrap : 0u);
         }
+        if (F.all_done)
+            n_done = cnt;
         if (accN)
             atomicAdd(&ev[cur], ((unsigned long long)accN << 32) +
                                     (unsigned long long)(long long)(int32_t)(accS - __umul24(accN, cur)));
@@ -700,6 +708,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         F.dbits = per_job_s ? 16u : 31u;
         F.sshift = F.dbits;
         F.has_s = per_job_s;
+        F.swidth = per_job_s ? 16u : 0u;
         F.all_done = true;
     } else {
         /* durations are at most max(o), or a slice of a level some job reaches */
@@ -716,6 +725,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         F.has_s = per_job_s && maxS_sh > 0; /* all-zero prompts need no field */
         F.all_done = false;
         const uint32_t sbits = F.has_s ? 32u - kvs_clz32(maxS_sh) : 0u;
+        F.swidth = sbits;
         const bool fits = F.dbits + 1u + sbits <= 32u;
         if (PACKED && !fits && flags == 0) {
             if (tid < G.n_pts)
@@ -725,6 +735,8 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         if (!PACKED && fits)
             return; /* not reachable: the one-word kernel has taken it */
     }
+
+    F.s_add = F.has_s ? 0u : J.s_scalar;
 
     /* ---- slots ---- */
     if (tid < kSlots) {
