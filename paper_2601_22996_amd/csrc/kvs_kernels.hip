@@ -331,7 +331,7 @@ constexpr unsigned long long kEndOne = 0xffffffff00000000ull;
  * ev: the wavefront's window of packed (C << 32) + A event sums, one per round of the slab.
  * sumF collects the start offsets of the completing runs that start here.
  */
-template <bool PACKED>
+template <bool PACKED, int WIN>
 __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool sps, uint32_t slab,
                                           const uint32_t *buf, uint32_t n_cap, uint32_t s_scalar,
                                           const EntryFmt &F, unsigned long long *ev, int lane,
@@ -339,7 +339,7 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
 {
     const uint32_t t_s = slab * sc.S;
     const uint32_t len = (sc.H - t_s < sc.S) ? (sc.H - t_s) : sc.S;
-    const int per = (int)((len + 63u) >> 6); /* window entries per lane, at most kWinMax / 64 */
+    const int per = (int)((len + 63u) >> 6); /* window entries per lane, at most WIN / 64 */
 
     for (int j = 0; j < per; j++)
         ev[j * 64 + lane] = 0ull;
@@ -432,8 +432,10 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
                                     (unsigned long long)(long long)(int32_t)(accS - __umul24(accN, cur)));
     }
     sumF += (unsigned long long)sum_st + (unsigned long long)n_done * (unsigned long long)t_s;
-    A0 = wave_sum(A0);
-    C0 = wave_sum(C0);
+    if (r0 < r1) { /* the same for every lane */
+        A0 = wave_sum(A0);
+        C0 = wave_sum(C0);
+    }
     if (!__any(touched)) {
         /* nothing starts or ends inside: the occupancy only grows, the last round is the largest */
         const int32_t occ = A0 + (int32_t)(len - 1u) * C0;
@@ -443,7 +445,7 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
-    constexpr int kPer = kWinMax / 64;
+    constexpr int kPer = WIN / 64; /* window entries per lane, at most */
     int32_t la[kPer], lc[kPer];
     int32_t sa = 0, sc_ = 0;
 #pragma unroll
@@ -876,7 +878,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
                 /* this wavefront's slabs: every NW-th, starting where the dealing has got to */
                 const uint32_t first = ((uint32_t)wave + NW - next_item % NW) % NW;
                 for (uint32_t j = first; j < sc.nslab; j += NW) {
-                    eval_slab<PACKED>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk, sumF);
+                    eval_slab<PACKED, WIN>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk, sumF);
                     mine = true;
                 }
                 next_item += sc.nslab;
