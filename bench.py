@@ -32,7 +32,8 @@ def kernel_source_digest():
     """sha256 over the sources the evaluation kernel is built from."""
     import hashlib
     h = hashlib.sha256()
-    for rel in ("paper_2601_22996_amd/csrc/kvs_kernels.hip", "paper_2601_22996_amd/csrc/kvs_math.h"):
+    for rel in ("paper_2601_22996_amd/csrc/kvs_kernels.hip", "paper_2601_22996_amd/csrc/kvs_phase.h",
+                "paper_2601_22996_amd/csrc/kvs_wave.h", "paper_2601_22996_amd/csrc/kvs_math.h"):
         with open(os.path.join(ROOT, rel), "rb") as f:
             h.update(f.read())
     return h.hexdigest()

@@ -7,7 +7,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SOURCES = [os.path.join(HERE, "csrc", "kvs_kernels.hip"), os.path.join(HERE, "csrc", "kvs_bounds.hip")]
-HEADERS = [os.path.join(HERE, "csrc", "kvs_math.h"), os.path.join(ROOT, "include", "kvsched.h")]
+HEADERS = [os.path.join(HERE, "csrc", h) for h in ("kvs_math.h", "kvs_wave.h", "kvs_phase.h")] + \
+          [os.path.join(ROOT, "include", "kvsched.h")]
 LIB = os.path.join(HERE, "libkvsched.so")
 
 HIPCC_FLAGS = [

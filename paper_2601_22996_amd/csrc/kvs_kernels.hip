@@ -35,6 +35,8 @@
 
 #include "kvsched.h"
 #include "kvs_math.h"
+#include "kvs_phase.h"
+#include "kvs_wave.h"
 
 namespace {
 
@@ -42,7 +44,6 @@ constexpr int kLevelsGeo = 32;         /* ladder levels base * 2^g that 2^30-bou
 constexpr int kLevelsMax = KVS_MAX_LEVELS; /* levels of an explicit ladder                              */
 constexpr int kMaxM = 8;               /* distinct shifts m per launch                                  */
 constexpr int kMaxV = 4;               /* distinct (subroutine, parallelism) variants per launch        */
-constexpr int kWinMax = 512;           /* most rounds a wavefront's window can hold                     */
 constexpr uint32_t kLenMax = 1u << 30; /* largest length the 32-bit arithmetic is sized for             */
 
 constexpr uint32_t FLAG_EINVAL = 1u;
@@ -82,31 +83,6 @@ struct OutsDev {
     int64_t *flow;
     int64_t *job_steps;
     int32_t *n_completed;
-};
-
-/* Slot: the jobs of one phase (a level, or the merged first phase of a shift). */
-struct Slot {
-    uint32_t n;     /* participants                                      */
-    uint32_t done;  /* of which complete in this phase                   */
-    uint32_t smax;  /* largest prompt among them                         */
-    uint32_t tau;   /* slice length                                      */
-    uint32_t off;   /* where its entries start in the phase buffer       */
-    uint32_t alias; /* slot whose results it shares, or its own index    */
-    kvs_divisor_t divtau; /* division by tau                             */
-};
-
-/* Variant of a slot: the schedule the subroutine builds on it. */
-struct Sched {
-    uint32_t k; /* parallelism (SPS) or batch size (SimS), >= 1          */
-    uint32_t H; /* rounds the phase lasts                                */
-    uint32_t S; /* slab length used to evaluate it                       */
-    uint32_t nslab;
-    kvs_divisor_t div;
-};
-
-struct Result {
-    int32_t peak;
-    unsigned long long sumF; /* sum of the start offsets of the completing runs */
 };
 
 /* What one job means on the ladder. */
@@ -185,326 +161,6 @@ __device__ __forceinline__ JobView view_job(const RawJob &r, const JobsDev &J, c
         v.gb = v.go;
     }
     return v;
-}
-
-/* Start offset of the r-th job of a phase: floor(r tau / k) for SPS
- * (Procedure 1), floor(r / k) tau for SimS. */
-__device__ __forceinline__ uint32_t start_offset(uint32_t r, uint32_t tau, const Sched &c, bool sps)
-{
-    return sps ? kvs_div(r * tau, c.div) : kvs_div(r, c.div) * tau;
-}
-
-/*
- * Number of runs of the phase whose start offset is below x, for x <= H.
- * SPS: floor(r tau / k) < x  <=>  r tau < x k  <=>  r < ceil(x k / tau).
- * SimS: floor(r / k) tau < x <=>  floor(r / k) < ceil(x / tau).
- * Past the last start offset the answer is n, which also keeps x * k inside
- * 31 bits: below it x k <= (n - 1) tau.
- */
-__device__ __forceinline__ uint32_t ranks_before(uint32_t x, const Slot &sl, const Sched &sc,
-                                                 bool sps)
-{
-    if (x == 0)
-        return 0;
-    if (x > sc.H - sl.tau)
-        return sl.n;
-    uint32_t r;
-    if (sps)
-        r = kvs_div(x * sc.k - 1u, sl.divtau) + 1u;
-    else
-        r = (kvs_div(x - 1u, sl.divtau) + 1u) * sc.k;
-    return r > sl.n ? sl.n : r;
-}
-
-__device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
-{
-    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-}
-
-/*
- * Wavefront-wide sums and maxima through the VALU's data-parallel lane moves
- * (DPP), which leave the LDS pipeline to the window atomics.  All 64 lanes
- * must be active.  Shifts by 1, 2, 4, 8 lanes inside each row of 16 build the
- * rows' prefixes; the last lane of row 0 / 2 is then broadcast into row
- * 1 / 3, and lane 31 into rows 2 and 3.
- */
-template <int CTRL, int ROWS>
-__device__ __forceinline__ int32_t dpp_take(int32_t fill, int32_t v)
-{
-    return __builtin_amdgcn_update_dpp(fill, v, CTRL, ROWS, 0xf, false);
-}
-
-/* inclusive prefix sum over the lanes */
-__device__ __forceinline__ int32_t wave_prefix_add(int32_t v)
-{
-    v += dpp_take<0x111, 0xf>(0, v); /* row_shr:1 */
-    v += dpp_take<0x112, 0xf>(0, v); /* row_shr:2 */
-    v += dpp_take<0x114, 0xf>(0, v); /* row_shr:4 */
-    v += dpp_take<0x118, 0xf>(0, v); /* row_shr:8 */
-    v += dpp_take<0x142, 0xa>(0, v); /* row_bcast:15 into rows 1 and 3 */
-    v += dpp_take<0x143, 0xc>(0, v); /* row_bcast:31 into rows 2 and 3 */
-    return v;
-}
-
-/* sum over the lanes, the same value in every lane */
-__device__ __forceinline__ int32_t wave_sum(int32_t v)
-{
-    return __builtin_amdgcn_readlane(wave_prefix_add(v), 63);
-}
-
-/* maximum over the lanes of values >= 0, the same value in every lane */
-__device__ __forceinline__ int32_t wave_max_nonneg(int32_t v)
-{
-    int32_t u;
-    u = dpp_take<0x111, 0xf>(0, v); v = u > v ? u : v;
-    u = dpp_take<0x112, 0xf>(0, v); v = u > v ? u : v;
-    u = dpp_take<0x114, 0xf>(0, v); v = u > v ? u : v;
-    u = dpp_take<0x118, 0xf>(0, v); v = u > v ? u : v;
-    u = dpp_take<0x142, 0xa>(0, v); v = u > v ? u : v;
-    u = dpp_take<0x143, 0xc>(0, v); v = u > v ? u : v;
-    return __builtin_amdgcn_readlane(v, 63);
-}
-
-/* sum over the lanes of 63-bit values, in three limbs of 21 bits */
-__device__ __forceinline__ unsigned long long wave_sum_u63(unsigned long long v)
-{
-    const uint32_t m = (1u << 21) - 1u;
-    const unsigned long long a = (uint32_t)wave_sum((int32_t)((uint32_t)v & m));
-    const unsigned long long b = (uint32_t)wave_sum((int32_t)((uint32_t)(v >> 21) & m));
-    const unsigned long long c = (uint32_t)wave_sum((int32_t)((uint32_t)(v >> 42) & m));
-    return a + (b << 21) + (c << 42);
-}
-
-/* How phase entries are laid out in LDS.  One word: prompt | done-bit |
- * duration, with the field width taken from the instance's largest values;
- * two words when that does not fit 32 bits. */
-struct EntryFmt {
-    uint32_t dbits;  /* duration in bits [0, dbits), done-bit at dbits, prompt above          */
-    uint32_t sshift; /* where the prompt starts: dbits + 1, or dbits when no done-bit is kept */
-    uint32_t swidth; /* bits of the prompt field, 0 when no prompt is stored                  */
-    uint32_t s_add;  /* the common prompt length when none is stored, else 0                  */
-    bool has_s;      /* per-job prompts are stored at all                                     */
-    bool all_done;   /* every run completes: no done-bit                                      */
-};
-
-template <bool PACKED>
-__device__ __forceinline__ void put_entry(uint32_t *buf, uint32_t n_cap, uint32_t pos, uint32_t d,
-                                          bool done, uint32_t s, const EntryFmt &F)
-{
-    if (PACKED) {
-        uint32_t w = d;
-        if (!F.all_done)
-            w |= (uint32_t)done << F.dbits;
-        if (F.has_s)
-            w |= s << F.sshift;
-        buf[pos] = w;
-    } else {
-        buf[pos] = d | ((uint32_t)done << 31);
-        buf[n_cap + pos] = s;
-    }
-}
-
-template <bool PACKED>
-__device__ __forceinline__ void get_entry(const uint32_t *buf, uint32_t n_cap, uint32_t pos,
-                                          uint32_t &d, bool &done, uint32_t &s, uint32_t s_scalar,
-                                          const EntryFmt &F)
-{
-    const uint32_t w = buf[pos];
-    if (PACKED) {
-        d = w & ((1u << F.dbits) - 1u);
-        done = F.all_done || ((w >> F.dbits) & 1u);
-        s = __builtin_amdgcn_ubfe(w, F.sshift, F.swidth) + F.s_add; /* width 0 extracts 0 */
-    } else {
-        d = w & 0x7fffffffu;
-        done = w >> 31;
-        s = buf[n_cap + pos];
-    }
-}
-
-/* An end event: one run less, and its weight w = s + 1 - start taken out: -(2^32 + w), as
- * this constant plus the sign-extended -w. */
-constexpr unsigned long long kEndOne = 0xffffffff00000000ull;
-
-/*
- * One slab [t_s, t_s + len) of one phase variant, by one wavefront.
- * ev: the wavefront's window of packed (C << 32) + A event sums, one per round of the slab.
- * sumF collects the start offsets of the completing runs that start here.
- */
-template <bool PACKED, int WIN>
-__device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool sps, uint32_t slab,
-                                          const uint32_t *buf, uint32_t n_cap, uint32_t s_scalar,
-                                          const EntryFmt &F, unsigned long long *ev, int lane,
-                                          int32_t &pk, unsigned long long &sumF)
-{
-    const uint32_t t_s = slab * sc.S;
-    const uint32_t len = (sc.H - t_s < sc.S) ? (sc.H - t_s) : sc.S;
-    const int per = (int)((len + 63u) >> 6); /* window entries per lane, at most WIN / 64 */
-
-    for (int j = 0; j < per; j++)
-        ev[j * 64 + lane] = 0ull;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-
-    /* ranks [r0, r1) started less than tau rounds before the slab, [r1, r2) start inside it */
-    const uint32_t r0 = ranks_before((t_s + 1u > sl.tau) ? (t_s + 1u - sl.tau) : 0u, sl, sc, sps);
-    const uint32_t r1 = ranks_before(t_s, sl, sc, sps);
-    const uint32_t r2 = ranks_before(t_s + len, sl, sc, sps);
-
-    int32_t A0 = 0, C0 = 0;
-    bool touched = (r2 > r1);
-    for (uint32_t r = r0 + lane; r < r1; r += 64) {
-        uint32_t d, s;
-        bool done;
-        get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F);
-        const int32_t st = (int32_t)(start_offset(r, sl.tau, sc, sps) - t_s); /* in (-tau, 0) */
-        const int32_t en = st + (int32_t)d;
-        if (en > 0) { /* still running when the slab begins */
-            const int32_t w = (int32_t)s + 1 - st;
-            A0 += w;
-            C0 += 1;
-            if (en < (int32_t)len) {
-                atomicAdd(&ev[en], kEndOne + (unsigned long long)(long long)(-w));
-                touched = true;
-            }
-        }
-    }
-    /* Runs that start inside the slab.  Each lane takes a block of consecutive ranks, so the
-     * runs of one round sit in one lane (two at a block's edge): their start events are summed
-     * in registers and added once, and different lanes work on different rounds -- no lane
-     * fights another for a window entry.  The block length is odd, which spreads the lanes'
-     * LDS reads over all banks. */
-    uint32_t sum_st = 0, n_done = 0; /* per lane: a few runs, offsets below the window size */
-    {
-        const uint32_t blk = ((r2 - r1 + 63u) >> 6) | 1u;
-        const uint32_t rb = r1 + (uint32_t)lane * blk;
-        /* inside a block the start offset is carried from rank to rank (quotient and
-         * remainder of r tau / k, or of r / k) instead of divided out each time */
-        uint32_t f = 0, rem = 0;
-        if (rb < r2) {
-            if (sps) {
-                f = kvs_div(rb * sl.tau, sc.div);
-                rem = rb * sl.tau - f * sc.k;
-            } else {
-                const uint32_t b = kvs_div(rb, sc.div);
-                f = b * sl.tau;
-                rem = rb - b * sc.k;
-            }
-        }
-        /* per rank: SPS adds tau to the remainder modulo k, SimS adds 1 modulo k (tau rounds per wrap) */
-        const uint32_t q_step = sps ? kvs_div(sl.tau, sc.div) : 0u;
-        const uint32_t r_step = sps ? sl.tau - q_step * sc.k : 1u;
-        const uint32_t wrap = sps ? 1u : sl.tau;
-        uint32_t cur = 0, accS = 0, accN = 0;
-        const uint32_t cnt = rb < r2 ? (r2 - rb < blk ? r2 - rb : blk) : 0u;
-        for (uint32_t j = 0; j < cnt; j++) {
-            uint32_t d, s;
-            bool done;
-            get_entry<PACKED>(buf, n_cap, sl.off + rb + j, d, done, s, s_scalar, F);
-            const uint32_t st = f - t_s; /* in [0, len) */
-            if (st != cur && accN) {
-                atomicAdd(&ev[cur], ((unsigned long long)accN << 32) +
-                                        (unsigned long long)(long long)(int32_t)(accS - __umul24(accN, cur)));
-                accS = 0;
-                accN = 0;
-            }
-            cur = st;
-            accS += s + 1u;
-            accN += 1u;
-            const uint32_t en = st + d;
-            if (en < len)
-                atomicAdd(&ev[en], kEndOne + (unsigned long long)(long long)(int32_t)(st - (s + 1u)));
-            if (F.all_done) {
-                sum_st += st;
-            } else {
-                sum_st += done ? st : 0u;
-                n_done += done ? 1u : 0u;
-            }
-            rem += r_step;
-            const bool over = rem >= sc.k;
-            rem -= over ? sc.k : 0u;
-            f += q_step + (over ? wrap : 0u);
-        }
-        if (F.all_done)
-            n_done = cnt;
-        if (accN)
-            atomicAdd(&ev[cur], ((unsigned long long)accN << 32) +
-                                    (unsigned long long)(long long)(int32_t)(accS - __umul24(accN, cur)));
-    }
-    sumF += (unsigned long long)sum_st + (unsigned long long)n_done * (unsigned long long)t_s;
-    if (r0 < r1) { /* the same for every lane */
-        A0 = wave_sum(A0);
-        C0 = wave_sum(C0);
-    }
-    if (!__any(touched)) {
-        /* nothing starts or ends inside: the occupancy only grows, the last round is the largest */
-        const int32_t occ = A0 + (int32_t)(len - 1u) * C0;
-        pk = occ > pk ? occ : pk;
-        return;
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-
-    constexpr int kPer = WIN / 64; /* window entries per lane, at most */
-    int32_t la[kPer], lc[kPer];
-    int32_t sa = 0, sc_ = 0;
-#pragma unroll
-    for (int j = 0; j < kPer; j++) {
-        const unsigned long long e = (j < per) ? ev[lane * per + j] : 0ull;
-        la[j] = (int32_t)(uint32_t)e;                        /* A, signed low word          */
-        lc[j] = (int32_t)(uint32_t)(e >> 32) - (la[j] >> 31); /* C: undo the low word's borrow */
-        sa += la[j];
-        sc_ += lc[j];
-    }
-    int32_t A = A0 + wave_prefix_add(sa) - sa;
-    int32_t C = C0 + wave_prefix_add(sc_) - sc_;
-#pragma unroll
-    for (int j = 0; j < kPer; j++) {
-        if (j < per) {
-            A += la[j];
-            C += lc[j];
-            const int32_t t = lane * per + j;
-            const int32_t occ = A + __mul24(t, C); /* t < 2^9, |C| < 2^23 by the range check */
-            if ((uint32_t)t < len && occ > pk)
-                pk = occ;
-        }
-    }
-}
-
-/*
- * A phase of at most 64 runs, by one wavefront, one run per lane.  The
- * occupancy can only fall right after a run's last round, so its maximum is
- * attained in the last round of some run: every lane evaluates the round in
- * which its own run ends, summing over all runs of the phase.
- */
-template <bool PACKED>
-__device__ __forceinline__ void eval_sparse(const Slot &sl, const Sched &sc, bool sps,
-                                            const uint32_t *buf, uint32_t n_cap, uint32_t s_scalar,
-                                            const EntryFmt &F, int lane, int32_t &pk,
-                                            unsigned long long &sumF)
-{
-    uint32_t d = 0, s = 0, f = 0;
-    bool done = false;
-    const bool act = (uint32_t)lane < sl.n;
-    if (act) {
-        get_entry<PACKED>(buf, n_cap, sl.off + (uint32_t)lane, d, done, s, s_scalar, F);
-        f = start_offset((uint32_t)lane, sl.tau, sc, sps);
-        if (done)
-            sumF += f;
-    }
-    const uint32_t s1 = s + 1u;
-    const uint32_t e = f + d;  /* first round after the run */
-    const uint32_t t = e - 1u; /* its last round            */
-    uint32_t occ = 0;
-    for (uint32_t q = 0; q < sl.n; q++) {
-        const uint32_t fq = __builtin_amdgcn_readlane(f, (int)q);
-        const uint32_t eq = __builtin_amdgcn_readlane(e, (int)q);
-        const uint32_t sq = __builtin_amdgcn_readlane(s1, (int)q);
-        if (fq <= t && t < eq)
-            occ += sq + (t - fq);
-    }
-    if (act && (int32_t)occ > pk)
-        pk = (int32_t)occ;
 }
 
 /* 768 threads: two workgroups per compute unit need 6 wavefronts per SIMD, i.e. at most 80 VGPRs. */
