@@ -56,10 +56,10 @@ def test_printed_values_and_hand_examples(K):
     assert ar[0] == 2 * 10 + 23                                   # ordered by area, not by length
 
 
-@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 257, 1000, 2048, 2049, 4100])
+@pytest.mark.parametrize("n", [1, 2, 15, 16, 17, 63, 64, 65, 257, 1000, 1024, 1025, 2048, 2049, 4096, 4097, 8193])
 def test_random_instances(K, n):
     rng = np.random.default_rng(1000 + n)
-    I = 24 if n <= 1000 else 6
+    I = 24 if n <= 1000 else (6 if n <= 4100 else 2)
     o = np.minimum(rng.geometric(1 / 40, (I, n)), 3000).astype(np.int32)
     o[0] = 1                                                      # a single class
     hetero = n % 2 == 1

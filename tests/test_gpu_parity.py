@@ -319,3 +319,26 @@ def test_workload5_full_size_sampled(K):
     tot = d["o"].sum(axis=1, dtype=np.int64)
     assert (first["job_steps"] == tot[None, :]).all()
     assert (first["flow"] >= tot[None, :]).all()
+
+
+def test_calls_on_a_side_stream_and_reused_outputs(K):
+    # the work goes to the stream that is passed; outputs allocated once are refilled in place
+    rng = np.random.default_rng(2718)
+    o = np.minimum(rng.geometric(1.0 / 50, (40, 1200)), 800).astype(np.int32)
+    s = rng.integers(0, 90, (40, 1200)).astype(np.int32)
+    pts = [(1, 0, 0, 0), (2, 1, 0, 0), (8, 0, 0, 1)]
+    want = O.gba_simulate_batch(o, s, 9000, pts)
+    do, ds = dev(o), dev(s)
+    side = torch.cuda.Stream()                      # default priority
+    side.wait_stream(torch.cuda.current_stream())   # the uploads above
+    out = K.gba_simulate(do, ds, 9000, pts, stream=side)
+    side.synchronize()
+    assert_same({k: v.cpu().numpy() for k, v in out.items()}, want)
+    for v in out.values():
+        v.fill_(77)
+    torch.cuda.current_stream().synchronize()
+    with torch.cuda.stream(side):                   # the binding's default: torch's current stream
+        again = K.gba_simulate(do, ds, 9000, pts, out=out)
+    side.synchronize()
+    assert again is out
+    assert_same({k: v.cpu().numpy() for k, v in out.items()}, want)
