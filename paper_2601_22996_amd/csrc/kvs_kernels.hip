@@ -235,6 +235,19 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
 
     /* ---- pass 1: per wavefront, how many of its jobs enter / leave at each level ---- */
     {
+        /* Most jobs fall into two or three levels, and lanes that add to the same counter are
+         * served one after the other.  The wavefront's window, idle until phases are evaluated,
+         * holds kRep copies of the entry histogram, one per group of lanes (rows one word longer
+         * than the levels, so equal levels of different copies sit in different banks). */
+        constexpr int kRowE = kLevels + 1;
+        constexpr int kRep = (2 * WIN / kRowE >= 8) ? 8 : (2 * WIN / kRowE >= 4) ? 4 : (2 * WIN / kRowE >= 2) ? 2 : 1;
+        static_assert(kRep * kRowE <= 2 * WIN, "histogram copies fit the window");
+        uint32_t *histE = reinterpret_cast<uint32_t *>(ev[wave]);
+        for (int i = lane; i < kRep * kRowE; i += 64)
+            histE[i] = 0;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        uint32_t *myE = histE + (lane & (kRep - 1)) * kRowE;
         unsigned long long sumO = 0;
         uint32_t mxO = 0, mxS = 0, mxG = 0;
         bool inval = false;
@@ -249,7 +262,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
             mxG = v.gb > mxG ? v.gb : mxG;
             if (PACKED && one_phase_each) /* the job as a phase entry, at its place in the input */
                 buf[i] = per_job_s ? ((v.s << 16) | (v.o & 0xffffu)) : v.o;
-            atomicAdd(&cumE[wave][v.ga], 1u); /* the wavefront's own histogram */
+            atomicAdd(&myE[v.ga], 1u); /* the wavefront's own histogram */
             if (!one_phase_each)
                 atomicAdd(&cumL[wave][v.gb], 1u);
             if (per_job_s) { /* the maxima settle after a few jobs; then this only reads */
@@ -307,7 +320,10 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        const uint32_t cntE = (lane < kLevels) ? cumE[wave][lane] : 0u;
+        uint32_t cntE = 0;
+        if (lane < kLevels)
+            for (int r = 0; r < kRep; r++)
+                cntE += histE[r * kRowE + lane];
         const uint32_t cntL = one_phase_each ? cntE : ((lane < kLevels) ? cumL[wave][lane] : 0u);
         /* inclusive prefix over levels (lanes 0..31 hold the levels) */
         uint32_t pe = cntE, pl = cntL;
