@@ -523,7 +523,18 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         }
         sched[vi][si] = sc;
         res[vi][si].peak = 0;
-        res[vi][si].sumF = 0;
+        /* Sum of the start offsets of the completing runs.  When every run completes it is a
+         * closed form of (n, tau, k) and nothing has to be summed over the runs. */
+        unsigned long long sumF0 = 0;
+        if (F.all_done && sl.n > 0 && (uint64_t)sl.n * sl.tau < (1ull << 31)) { /* else out of range: 1 <= k <= n tau needs it */
+            if (sps) {
+                sumF0 = kvs_floor_sum(sl.n, sc.k, sl.tau);
+            } else {
+                const uint64_t q = sl.n / sc.k, rem = sl.n - q * sc.k; /* q whole batches, then rem jobs */
+                sumF0 = (uint64_t)sl.tau * ((uint64_t)sc.k * (q * (q - 1u) / 2u) + q * rem);
+            }
+        }
+        res[vi][si].sumF = sumF0;
     }
     __syncthreads();
 
@@ -557,10 +568,12 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
             }
             if (mine) {
                 pk = wave_max_nonneg(pk);
-                sumF = wave_sum_u63(sumF);
-                if (lane == 0) {
+                if (lane == 0)
                     atomicMax(&res[vi][si].peak, pk);
-                    atomicAdd(&res[vi][si].sumF, sumF);
+                if (!F.all_done) { /* else the table holds the closed form */
+                    sumF = wave_sum_u63(sumF);
+                    if (lane == 0)
+                        atomicAdd(&res[vi][si].sumF, sumF);
                 }
             }
         }

@@ -121,4 +121,35 @@ KVS_HD uint64_t kvs_kstar(uint64_t tau, uint64_t s, uint64_t M)
     return K - 1u;
 }
 
+/*
+ * sum_{i = 0}^{n-1} floor(i * tau / k): the start offsets of Procedure 1 summed
+ * over a phase of n jobs (the second part of the ladder term Q_p in the analysis
+ * of GBA).  Euclid-like reduction: whole multiples of k in tau are summed in
+ * closed form, then the lattice points under the line are counted from the
+ * other axis, which swaps the roles of tau and k; O(log) steps.  Needs k >= 1
+ * and a result below 2^63 (n <= 2^14, tau < 2^31, k < 2^41 are safe).
+ */
+KVS_HD uint64_t kvs_floor_sum(uint64_t n, uint64_t k, uint64_t tau)
+{
+    uint64_t ans = 0, a = tau, m = k, b = 0;
+    for (;;) {
+        if (a >= m) {
+            ans += (n - 1u) * n / 2u * (a / m);
+            a %= m;
+        }
+        if (b >= m) {
+            ans += n * (b / m);
+            b %= m;
+        }
+        uint64_t y = a * n + b;
+        if (y < m)
+            return ans;
+        n = y / m;
+        b = y % m;
+        uint64_t t = m;
+        m = a;
+        a = t;
+    }
+}
+
 #endif /* KVS_MATH_H */
