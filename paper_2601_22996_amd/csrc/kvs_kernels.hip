@@ -164,7 +164,7 @@ __device__ __forceinline__ JobView view_job(const RawJob &r, const JobsDev &J, c
 }
 
 /* 768 threads: two workgroups per compute unit need 6 wavefronts per SIMD, i.e. at most 80 VGPRs. */
-template <int T, bool PACKED, int WIN, int LV, int HOLD>
+template <int T, bool PACKED, bool NESTED, int WIN, int LV, int HOLD>
 __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDev J, GroupArg G, OutsDev out)
 {
     constexpr int NW = T / 64;
@@ -172,6 +172,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
     constexpr int kSlots = LV + kMaxM;   /* phase slots: one per level, one per merged first phase */
     constexpr bool EXPLICIT = (LV == kLevelsMax); /* explicit ladders get the large instantiation */
     static_assert(LV == kLevelsGeo || LV == kLevelsMax, "levels");
+    static_assert(PACKED || !NESTED, "the LDS-only path works on one-word entries");
 
     extern __shared__ uint32_t buf[]; /* phase entries: n_jobs words, twice that when !PACKED */
 
@@ -260,7 +261,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
             mxO = v.o > mxO ? v.o : mxO;
             mxS = v.s > mxS ? v.s : mxS;
             mxG = v.gb > mxG ? v.gb : mxG;
-            if (PACKED && one_phase_each) /* the job as a phase entry, at its place in the input */
+            if (NESTED) /* the job as a phase entry, at its place in the input */
                 buf[i] = per_job_s ? ((v.s << 16) | (v.o & 0xffffu)) : v.o;
             atomicAdd(&myE[v.ga], 1u); /* the wavefront's own histogram */
             if (!one_phase_each)
@@ -375,8 +376,13 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
     /* One phase per job and values narrow enough for the copy pass 1 left in LDS (duration in
      * 16 bits under a 16-bit prompt, or a bare duration): every phase's entries are then cut out
      * of that copy inside LDS and the jobs are not read from memory again. */
-    const bool nested = PACKED && one_phase_each && G.mode != MODE_SINGLE &&
-                        (!per_job_s || (maxO_sh < 65536u && maxS_sh < 65536u));
+    constexpr bool nested = NESTED; /* launched only when every job has one phase (no estimates, GBA) */
+    if (NESTED && per_job_s && (maxO_sh >= 65536u || maxS_sh >= 65536u) && flags == 0) {
+        /* too wide for the copy: left to the kernel with two-word entries */
+        if (tid < G.n_pts)
+            out.feasible[(size_t)G.pt_q[tid] * (size_t)J.n_inst + inst] = FEASIBLE_PENDING;
+        return;
+    }
     EntryFmt F;
     if (nested) {
         F.dbits = per_job_s ? 16u : 31u;
@@ -406,8 +412,6 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
                 out.feasible[(size_t)G.pt_q[tid] * (size_t)J.n_inst + inst] = FEASIBLE_PENDING;
             return;
         }
-        if (!PACKED && fits)
-            return; /* not reachable: the one-word kernel has taken it */
     }
 
     F.s_add = F.has_s ? 0u : J.s_scalar;
@@ -951,12 +955,12 @@ JobsDev to_dev(const kvs_jobs_t *jobs, bool use_estimates)
     return J;
 }
 
-template <int T, bool PACKED, int WIN, int LV, int HOLD>
+template <int T, bool PACKED, bool NESTED, int WIN, int LV, int HOLD>
 int32_t launch_sweep(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
 {
     const size_t lds = sizeof(uint32_t) * (size_t)J.n_jobs * (PACKED ? 1 : 2);
-    static_assert(!PACKED || HOLD * T >= (T == 256 ? 4096 : 1), "hold");
-    auto kern = kvs_sweep_kernel<T, PACKED, WIN, LV, HOLD>;
+    static_assert(!NESTED || HOLD * T >= (T == 256 ? 4096 : 1), "hold");
+    auto kern = kvs_sweep_kernel<T, PACKED, NESTED, WIN, LV, HOLD>;
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return KVS_EHIP;
@@ -964,31 +968,41 @@ int32_t launch_sweep(const JobsDev &J, const GroupArg &G, const OutsDev &out, hi
     return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
 }
 
-int32_t run_group(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
+/*
+ * First launch: one-word entries.  When every job has exactly one phase (GBA on true
+ * lengths) the instantiation that cuts all phases out of one LDS copy, else the one that
+ * compacts each phase from memory.  Second launch, only with per-job prompts: the instances
+ * the first one marked as too wide, with two-word entries.
+ */
+template <int LV>
+int32_t run_group_lv(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
 {
     int32_t rc;
     const bool big = J.n_jobs > 4096;
+    const bool one_phase_each = (G.mode == MODE_GBA) && (J.e == nullptr);
     /* registers a thread needs to hold its share of an instance: n_jobs / threads, rounded up */
     constexpr int kHoldMid = 14, kHoldMax = (KVS_MAX_JOBS + 767) / 768;
     const bool mid = J.n_jobs <= kHoldMid * 768;
-    if (G.n_lv > 0) { /* explicit ladder: the instantiation with room for KVS_MAX_LEVELS levels */
-        rc = big ? launch_sweep<768, true, 256, kLevelsMax, kHoldMax>(J, G, out, st)
-                 : launch_sweep<256, true, 384, kLevelsMax, 16>(J, G, out, st);
-        if (rc != KVS_OK || !J.s)
-            return rc;
-        return big ? launch_sweep<512, false, 128, kLevelsMax, 1>(J, G, out, st)
-                   : launch_sweep<256, false, 256, kLevelsMax, 1>(J, G, out, st);
-    }
     /* Large instances: 12 wavefronts and 256-round windows keep two workgroups (24 wavefronts)
      * on a compute unit next to a 40 KB phase buffer; measured best among the shapes tried. */
-    rc = !big ? launch_sweep<256, true, 384, kLevelsGeo, 16>(J, G, out, st)
-         : mid ? launch_sweep<768, true, 256, kLevelsGeo, kHoldMid>(J, G, out, st)
-               : launch_sweep<768, true, 256, kLevelsGeo, kHoldMax>(J, G, out, st);
+    if (one_phase_each)
+        rc = !big ? launch_sweep<256, true, true, 384, LV, 16>(J, G, out, st)
+             : mid ? launch_sweep<768, true, true, 256, LV, kHoldMid>(J, G, out, st)
+                   : launch_sweep<768, true, true, 256, LV, kHoldMax>(J, G, out, st);
+    else
+        rc = !big ? launch_sweep<256, true, false, 384, LV, 1>(J, G, out, st)
+                  : launch_sweep<768, true, false, 256, LV, 1>(J, G, out, st);
     if (rc != KVS_OK || !J.s)
         return rc;
-    /* per-job prompts too wide for one-word entries: second pass over the marked instances */
-    return big ? launch_sweep<512, false, 256, kLevelsGeo, 1>(J, G, out, st)
-               : launch_sweep<256, false, 256, kLevelsGeo, 1>(J, G, out, st);
+    constexpr int kWinBig = (LV == kLevelsMax) ? 128 : 256; /* 16384 two-word entries fill most of LDS */
+    return big ? launch_sweep<512, false, false, kWinBig, LV, 1>(J, G, out, st)
+               : launch_sweep<256, false, false, 256, LV, 1>(J, G, out, st);
+}
+
+int32_t run_group(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
+{
+    /* explicit ladder: the instantiations with room for KVS_MAX_LEVELS levels */
+    return G.n_lv > 0 ? run_group_lv<kLevelsMax>(J, G, out, st) : run_group_lv<kLevelsGeo>(J, G, out, st);
 }
 
 struct HostPoint {
