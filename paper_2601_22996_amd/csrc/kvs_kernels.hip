@@ -651,7 +651,8 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
                 break; /* the rest of the stretch is empty (the same for all lanes) */
             const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
             held[c] = (idx < hi) ? buf[idx] : 0xffffffffu;
-            kept += (uint32_t)__popcll(__ballot(idx < hi && (held[c] & dmask) <= theta));
+            const bool keep = idx < hi && (held[c] & dmask) <= theta;
+            kept += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(keep));
         }
         if (lane == 0)
             wkeep[wave] = kept;
@@ -669,16 +670,21 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         }
 #pragma unroll
         for (int c = 0; c < kHold; c++) {
-            if (lo + (uint32_t)c * 64u >= hi)
+            const uint32_t at = lo + (uint32_t)c * 64u;
+            if (at >= hi)
                 break; /* the rest of the stretch is empty (the same for all lanes) */
-            const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
-            const bool act = idx < hi;
+            /* the entries of a chunk sit in its first lanes, so a lane's rank among them is its
+             * number, and its rank among the moved ones is that minus its rank among the kept */
+            const bool act = at + (uint32_t)lane < hi;
             const bool keep = act && (held[c] & dmask) <= theta;
-            const uint64_t bk = __ballot(keep), bm = __ballot(act && !keep);
+            const uint64_t bk = __builtin_amdgcn_ballot_w64(keep);
+            const uint32_t rk = lanes_below(bk);
             if (act)
-                buf[keep ? front + lanes_below(bk) : back + lanes_below(bm)] = held[c];
-            front += (uint32_t)__popcll(bk);
-            back += (uint32_t)__popcll(bm);
+                buf[keep ? front + rk : back + ((uint32_t)lane - rk)] = held[c];
+            const uint32_t nk = (uint32_t)__popcll(bk);
+            const uint32_t na = hi - at < 64u ? hi - at : 64u;
+            front += nk;
+            back += na - nk;
         }
         __syncthreads();
     };
