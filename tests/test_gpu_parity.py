@@ -342,3 +342,27 @@ def test_calls_on_a_side_stream_and_reused_outputs(K):
     side.synchronize()
     assert again is out
     assert_same({k: v.cpu().numpy() for k, v in out.items()}, want)
+
+
+def test_replayed_from_a_captured_graph(K):
+    # the evaluation calls allocate nothing and only launch kernels, so a caller may capture them
+    # into a graph; every replay is checked, with eager work between the replays
+    rng = np.random.default_rng(1618)
+    pts = [(1, 0, 0, 0), (4, 1, 0, 0), (2, 0, 0, 1)]
+    M = 12000
+    batches = [np.minimum(rng.geometric(1.0 / 70, (24, 1500)), 900).astype(np.int32) for _ in range(3)]
+    s = rng.integers(0, 120, (24, 1500)).astype(np.int32)
+    do, ds = dev(batches[0]), dev(s)
+    out = K.gba_simulate(do, ds, M, pts)             # eager: allocates the outputs, loads the kernels
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        K.gba_simulate(do, ds, M, pts, out=out)
+    for o in batches[1:] + batches[:1]:
+        do.copy_(torch.from_numpy(o))                # eager work between the replays
+        for v in out.values():
+            v.fill_(3)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_same({k: v.cpu().numpy() for k, v in out.items()}, O.gba_simulate_batch(o, s, M, pts))
