@@ -33,6 +33,21 @@
  * and re-enters the next phase (Procedure 1's kill rule with Algorithm 1's
  * "keep the unfinished jobs").
  *
+ * What pins what (tests/test_oracle_pins.py).  The stepper, SPS, SimS and
+ * k*: the printed values of the toy example (180, 225, peak 15), the Peak
+ * lemma against the stepped peak, the identical-jobs flow identity.  The
+ * phase driver in GBA and GSA mode: the printed 14083 and 21632 of the uniform
+ * experiment, the long-job closed form, the two-point experiment's bracket, a
+ * second driver written independently, the ratio theorems against exhaustive
+ * search.  The ladder of Algorithms 1 and 2: exact rational arithmetic.  The
+ * bounds (kvo_upper_gba, kvo_area_lb): printed values, hand examples, the
+ * lemmas as inequalities against the stepped flow and the exhaustive optimum.
+ * Parity unpinned by anything the paper prints: the treatment of estimates
+ * other than the two ends (estimate = true length, estimate = 1) to which it
+ * reduces; per-job prompt lengths (only the invariant MemPeak <= M); the
+ * order of the jobs inside a phase; a job shorter than its slice leaving the
+ * later starts where they are.
+ *
  * All quantities are integers (tokens, rounds); 64-bit throughout.
  */
 #include <stdint.h>
