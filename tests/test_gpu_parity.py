@@ -366,3 +366,25 @@ def test_replayed_from_a_captured_graph(K):
         graph.replay()
         torch.cuda.synchronize()
         assert_same({k: v.cpu().numpy() for k, v in out.items()}, O.gba_simulate_batch(o, s, M, pts))
+
+
+def test_calls_overlapping_on_two_streams(K):
+    # the library keeps no state between or across calls: two calls in flight at once, on
+    # different streams and different inputs, do not disturb each other
+    rng = np.random.default_rng(31415)
+    pts = [(1, 0, 0, 0), (8, 1, 0, 0)]
+    jobs = []
+    for j in range(2):
+        o = np.minimum(rng.geometric(1.0 / 60, (512, 3000)), 1500).astype(np.int32)
+        s = rng.integers(0, 200, (512, 3000)).astype(np.int32)
+        jobs.append((o, s, dev(o), dev(s)))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = []
+    for rep in range(3):
+        outs = [K.gba_simulate(j[2], j[3], 40000, pts, stream=st) for j, st in zip(jobs, streams)]
+    torch.cuda.synchronize()
+    idx = np.arange(0, 512, 37)
+    for j, out in zip(jobs, outs):
+        want = O.gba_simulate_batch(j[0][idx], j[1][idx], 40000, pts)
+        assert_same({k: v.cpu().numpy()[:, idx] for k, v in out.items()}, want)
