@@ -850,46 +850,72 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         }
     }
 
-    /* ---- put the phases of every point together ---- */
-    if (tid < G.n_pts) {
-        const int vi = G.pt_v[tid];
-        const int mi = G.pt_m[tid];
-        int64_t begin = 0, flow = (int64_t)sumO_sh, steps = (int64_t)sumO_sh, peak = 0;
-        int64_t done = 0;
-        if (!bad) {
-            int si = kLevels + mi;
-            const int last = (G.mode == MODE_SINGLE) ? 0 : kLevels - 1;
-            for (int g = (int)G.m[mi]; g <= last; g++, si = g) {
-                const Slot sl = slot[si];
-                if (sl.n == 0)
-                    continue;
+    /* ---- put the phases of every point together ----
+     * kLevels consecutive lanes per point: lane 0 takes the merged first phase, lane j the level
+     * m + j.  A phase begins when the ones before it have ended (prefix sum of the phase lengths
+     * over the lanes); flow = sum o + sum_p (done_p begin_p + start offsets of the completing
+     * runs), job steps = sum o + sum_p tau_p (n_p - done_p), peak = max_p. */
+    for (int item0 = 0; item0 < (int)G.n_pts * kLevels; item0 += T) {
+        const int item = item0 + tid;
+        const int q = item / kLevels, j = item % kLevels;
+        const bool have = q < (int)G.n_pts;
+        const int vi = have ? G.pt_v[q] : 0;
+        const int mi = have ? G.pt_m[q] : 0;
+        const int g = (int)G.m[mi] + j;
+        const bool in_ladder = have && !bad && (j == 0 || (G.mode != MODE_SINGLE && g < kLevels));
+        unsigned long long H = 0, sumF = 0;
+        uint32_t n_p = 0, done_p = 0, tau_p = 0;
+        int32_t pk = 0;
+        if (in_ladder) {
+            const Slot sl = slot[j == 0 ? kLevels + mi : g];
+            if (sl.n > 0) {
                 const Result r = res[vi][sl.alias];
-                flow += (int64_t)sl.done * begin + (int64_t)r.sumF;
-                steps += (int64_t)sl.tau * (int64_t)(sl.n - sl.done); /* killed runs use their whole slice */
-                done += sl.done;
-                peak = r.peak > peak ? r.peak : peak;
-                begin += sched[vi][sl.alias].H;
+                n_p = sl.n;
+                done_p = sl.done;
+                tau_p = sl.tau;
+                sumF = r.sumF;
+                pk = r.peak;
+                H = sched[vi][sl.alias].H;
             }
         }
-        uint8_t feas = (peak <= (int64_t)J.M) ? 1 : 0;
-        if (flags & FLAG_EINVAL)
-            feas = KVS_FEASIBLE_EINVAL;
-        else if (flags & FLAG_ERANGE)
-            feas = KVS_FEASIBLE_ERANGE;
-        if (bad) {
-            peak = -1;
-            flow = -1;
-            steps = -1;
-            done = -1;
+        unsigned long long begin = H; /* inclusive prefix over the point's lanes, then exclusive */
+#pragma unroll
+        for (int d = 1; d < kLevels; d <<= 1) {
+            const unsigned long long up = __shfl_up(begin, d, kLevels);
+            if (j >= d)
+                begin += up;
         }
-        const size_t oi = (size_t)G.pt_q[tid] * (size_t)J.n_inst + inst;
-        out.peak[oi] = peak;
-        out.feasible[oi] = feas;
-        out.flow[oi] = flow;
-        if (out.job_steps)
-            out.job_steps[oi] = steps;
-        if (out.n_completed)
-            out.n_completed[oi] = (int32_t)done;
+        begin -= H;
+        unsigned long long flow = (unsigned long long)done_p * begin + sumF;
+        unsigned long long steps = (unsigned long long)tau_p * (unsigned long long)(n_p - done_p); /* killed runs use their whole slice */
+        uint32_t done = done_p;
+#pragma unroll
+        for (int d = kLevels / 2; d >= 1; d >>= 1) {
+            flow += __shfl_xor(flow, d, kLevels);
+            steps += __shfl_xor(steps, d, kLevels);
+            done += __shfl_xor(done, d, kLevels);
+            const int32_t other = __shfl_xor(pk, d, kLevels);
+            pk = other > pk ? other : pk;
+        }
+        if (have && j == 0) {
+            int64_t peak = pk, fl = (int64_t)(flow + sumO_sh), st = (int64_t)(steps + sumO_sh);
+            int64_t dn = done;
+            uint8_t feas = (peak <= (int64_t)J.M) ? 1 : 0;
+            if (flags & FLAG_EINVAL)
+                feas = KVS_FEASIBLE_EINVAL;
+            else if (flags & FLAG_ERANGE)
+                feas = KVS_FEASIBLE_ERANGE;
+            if (bad)
+                peak = fl = st = dn = -1;
+            const size_t oi = (size_t)G.pt_q[q] * (size_t)J.n_inst + inst;
+            out.peak[oi] = peak;
+            out.feasible[oi] = feas;
+            out.flow[oi] = fl;
+            if (out.job_steps)
+                out.job_steps[oi] = st;
+            if (out.n_completed)
+                out.n_completed[oi] = (int32_t)dn;
+        }
     }
 }
 
