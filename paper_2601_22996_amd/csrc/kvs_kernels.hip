@@ -132,7 +132,7 @@ __device__ __forceinline__ uint32_t level_of(uint32_t x, const GroupArg &G, cons
 
 template <bool EXPLICIT>
 __device__ __forceinline__ JobView view_job(const RawJob &r, const JobsDev &J, const GroupArg &G,
-                                            const uint32_t *lad)
+                                            const uint32_t *lad, int mode, bool with_estimates)
 {
     JobView v;
     const int32_t o = r.o;
@@ -142,10 +142,10 @@ __device__ __forceinline__ JobView view_job(const RawJob &r, const JobsDev &J, c
     v.o = (o < 1) ? 1u : ((uint32_t)o > kLenMax ? kLenMax : (uint32_t)o);
     v.s = (s < 0) ? 0u : ((uint32_t)s > kLenMax ? kLenMax : (uint32_t)s);
     v.go = level_of<EXPLICIT>(v.o, G, lad, v.valid);
-    if (G.mode != MODE_GBA) { /* GSA, or one invocation of the subroutine: everybody from the start */
+    if (mode != MODE_GBA) { /* GSA, or one invocation of the subroutine: everybody from the start */
         v.ga = 0;
         v.gb = v.go;
-    } else if (J.e) {
+    } else if (with_estimates) {
         const int32_t e = r.e;
         v.valid = v.valid && (e >= 1);
         uint64_t cap = (J.M > v.s) ? (J.M - v.s) : 1u; /* M - s, at least 1 */
@@ -197,7 +197,11 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
     const uint32_t n = (uint32_t)J.n_jobs;
     const size_t row = (size_t)inst * n;
     const bool per_job_s = (J.s != nullptr);
-    const bool one_phase_each = (G.mode == MODE_GBA) && (J.e == nullptr);
+    /* the one-phase instantiation is launched only for GBA on true lengths: saying so here lets
+     * the compiler drop the other modes from it */
+    const int mode = NESTED ? MODE_GBA : (int)G.mode;
+    const bool with_estimates = !NESTED && mode == MODE_GBA && J.e != nullptr;
+    const bool one_phase_each = NESTED || (mode == MODE_GBA && J.e == nullptr);
     const uint32_t m_min = G.m[0];
 
     if (!PACKED) {
@@ -252,11 +256,11 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         unsigned long long sumO = 0;
         uint32_t mxO = 0, mxS = 0, mxG = 0;
         bool inval = false;
-        const bool want_e = (G.mode == MODE_GBA) && (J.e != nullptr);
+        const bool want_e = with_estimates;
         auto account = [&](const RawJob &raw, uint32_t i) {
-            const JobView v = view_job<EXPLICIT>(raw, J, G, lad);
+            const JobView v = view_job<EXPLICIT>(raw, J, G, lad, mode, with_estimates);
             inval |= !v.valid;
-            if (G.mode != MODE_SINGLE || v.go == 0)
+            if (mode != MODE_SINGLE || v.go == 0)
                 sumO += v.o; /* every job completes once; a lone invocation completes o <= tau */
             mxO = v.o > mxO ? v.o : mxO;
             mxS = v.s > mxS ? v.s : mxS;
@@ -430,7 +434,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         bool used = false;
         if (tid < kLevels) {
             lv = (uint32_t)tid;
-            used = (G.mode != MODE_SINGLE) && (lv > m_min);
+            used = (mode != MODE_SINGLE) && (lv > m_min);
             if (used) {
                 uint32_t enter = 0, left = 0, off = 0;
                 for (uint32_t l = 0; l <= lv; l++)
@@ -463,7 +467,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
             if (per_job_s)
                 sl.smax = sm;
             /* nobody from below: the merged phase is the level's own phase */
-            if (G.mode != MODE_SINGLE && lv > m_min && below == 0)
+            if (mode != MODE_SINGLE && lv > m_min && below == 0)
                 sl.alias = lv;
         }
         if (used && sl.n > 0) {
@@ -594,7 +598,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         }
         /* Pass 1 has vouched for the instance's values, so membership is two comparisons with
          * slices: entry level <= lv  <=>  believed length <= tau_lv, and so on. */
-        const bool want_e = (G.mode == MODE_GBA) && (J.e != nullptr);
+        const bool want_e = with_estimates;
         const uint32_t tau_lv = lad[lv];
         const uint32_t tau_below = lv ? lad[lv - 1] : 0u;
         RawJob nxt;
@@ -610,7 +614,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
             const uint32_t o = (uint32_t)raw.o, s = (uint32_t)raw.s;
             if (i < seg_hi) {
                 uint32_t bel = 1u; /* what the scheduler believes: GSA and lone invocations take everybody */
-                if (G.mode == MODE_GBA) {
+                if (mode == MODE_GBA) {
                     bel = o;
                     if (want_e) {
                         uint64_t cap = J.M - s;
@@ -779,7 +783,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
             for (int si = (int)m_min + 1; si < kLevels; si++)
                 eval_slot(si);
             __syncthreads();
-        } else if (one_phase_each && G.mode != MODE_SINGLE) {
+        } else if (one_phase_each && mode != MODE_SINGLE) {
             /* ---- stable multisplit by level: every level's jobs side by side, input order ---- */
             uint32_t cur = 0; /* lane l: next free position of level l for this wavefront */
             if (lane < kLevels) {
@@ -828,7 +832,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
             for (int si = (int)m_min + 1; si < kLevels; si++)
                 eval_slot(si);
             __syncthreads();
-        } else if (G.mode != MODE_SINGLE) {
+        } else if (mode != MODE_SINGLE) {
             for (int si = (int)m_min + 1; si < kLevels; si++) {
                 if (slot[si].n == 0)
                     continue;
@@ -862,7 +866,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         const int vi = have ? G.pt_v[q] : 0;
         const int mi = have ? G.pt_m[q] : 0;
         const int g = (int)G.m[mi] + j;
-        const bool in_ladder = have && !bad && (j == 0 || (G.mode != MODE_SINGLE && g < kLevels));
+        const bool in_ladder = have && !bad && (j == 0 || (mode != MODE_SINGLE && g < kLevels));
         unsigned long long H = 0, sumF = 0;
         uint32_t n_p = 0, done_p = 0, tau_p = 0;
         int32_t pk = 0;
