@@ -46,6 +46,12 @@
  * 2^30; 1 <= M < 2^40; per phase, n_p * tau_p < 2^31 and
  * min(n_p, k_p) * (s_max + tau_p + 513) < 2^31 (n_p jobs take part in the
  * phase, tau_p is its slice, k_p its parallelism, s_max its largest prompt).
+ *
+ * Cost: a phase of n_p jobs that lasts H_p rounds costs O(n_p + H_p / 64) per
+ * (subroutine, parallelism) variant; phases of at most 64 jobs cost O(n_p^2)
+ * whatever their length.  Schedules that are long and thin at once (more than
+ * 64 jobs per phase, slices in the millions, parallelism forced to a handful)
+ * are evaluated correctly but take time in proportion to their rounds.
  */
 #ifndef KVSCHED_H
 #define KVSCHED_H
