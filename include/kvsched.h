@@ -48,10 +48,9 @@
  * phase, tau_p is its slice, k_p its parallelism, s_max its largest prompt).
  *
  * Cost: a phase of n_p jobs that lasts H_p rounds costs O(n_p + H_p / 64) per
- * (subroutine, parallelism) variant; phases of at most 64 jobs cost O(n_p^2)
- * whatever their length.  Schedules that are long and thin at once (more than
- * 64 jobs per phase, slices in the millions, parallelism forced to a handful)
- * are evaluated correctly but take time in proportion to their rounds.
+ * (subroutine, parallelism) variant, or O(n_p k_p) where that is less (long
+ * slices with few jobs in flight); phases of at most 64 jobs cost O(n_p^2).
+ * No cost grows with the number of rounds alone.
  */
 #ifndef KVSCHED_H
 #define KVSCHED_H

@@ -528,6 +528,13 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
             }
             sc.S = S;
             sc.nslab = (sc.H + S - 1) / S;
+            /* Long and thin: evaluating every run against the at most k + 1 runs around it is
+             * cheaper than walking the rounds once a run's share of them, tau / k, is above a few
+             * times k (a slab of S rounds costs about as much as 20 runs' neighbours). */
+            if (sc.k * (uint64_t)sc.k < 4u * tau && sl.n > 64u) {
+                sc.S = 0;
+                sc.nslab = (sl.n + 63u) / 64u;
+            }
         }
         sched[vi][si] = sc;
         res[vi][si].peak = 0;
@@ -569,7 +576,10 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
                 /* this wavefront's slabs: every NW-th, starting where the dealing has got to */
                 const uint32_t first = ((uint32_t)wave + NW - next_item % NW) % NW;
                 for (uint32_t j = first; j < sc.nslab; j += NW) {
-                    eval_slab<PACKED, WIN>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk, sumF);
+                    if (sc.S == 0)
+                        eval_thin<PACKED>(sl, sc, sps, j, buf, n, J.s_scalar, F, lane, pk, sumF);
+                    else
+                        eval_slab<PACKED, WIN>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk, sumF);
                     mine = true;
                 }
                 next_item += sc.nslab;

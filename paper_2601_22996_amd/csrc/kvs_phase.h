@@ -35,8 +35,8 @@ struct Slot {
 struct Sched {
     uint32_t k; /* parallelism (SPS) or batch size (SimS), >= 1          */
     uint32_t H; /* rounds the phase lasts                                */
-    uint32_t S; /* slab length used to evaluate it                       */
-    uint32_t nslab;
+    uint32_t S; /* slab length used to evaluate it; 0: by runs, not by rounds (eval_thin) */
+    uint32_t nslab; /* work items: slabs of S rounds, or groups of 64 runs */
     kvs_divisor_t div;
 };
 
@@ -302,6 +302,44 @@ __device__ __forceinline__ void eval_sparse(const Slot &sl, const Sched &sc, boo
             occ += sq + (t - fq);
     }
     if (act && (int32_t)occ > pk)
+        pk = (int32_t)occ;
+}
+
+/*
+ * 64 consecutive runs of a phase that is long and thin (many more rounds than runs in
+ * flight): one run per lane, evaluated like eval_sparse in the last round of the lane's own
+ * run, but summing only over the runs that can be active then -- those that started less
+ * than tau rounds before that round, a contiguous stretch of at most k + 1 ranks.
+ * Cost O(k) per run instead of O(rounds / 64) per phase.
+ */
+template <bool PACKED>
+__device__ __forceinline__ void eval_thin(const Slot &sl, const Sched &sc, bool sps, uint32_t group,
+                                          const uint32_t *buf, uint32_t n_cap, uint32_t s_scalar,
+                                          const EntryFmt &F, int lane, int32_t &pk,
+                                          unsigned long long &sumF)
+{
+    const uint32_t r = group * 64u + (uint32_t)lane;
+    if (r >= sl.n)
+        return;
+    uint32_t d, s;
+    bool done;
+    get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F);
+    const uint32_t f = start_offset(r, sl.tau, sc, sps);
+    if (done)
+        sumF += f;
+    const uint32_t t = f + d - 1u; /* the run's last round */
+    const uint32_t q_lo = ranks_before(t + 1u > sl.tau ? t + 1u - sl.tau : 0u, sl, sc, sps);
+    const uint32_t q_hi = ranks_before(t + 1u, sl, sc, sps);
+    uint32_t occ = 0;
+    for (uint32_t q = q_lo; q < q_hi; q++) {
+        uint32_t dq, sq;
+        bool doneq;
+        get_entry<PACKED>(buf, n_cap, sl.off + q, dq, doneq, sq, s_scalar, F);
+        const uint32_t fq = start_offset(q, sl.tau, sc, sps);
+        if (fq <= t && t < fq + dq)
+            occ += sq + 1u + (t - fq);
+    }
+    if ((int32_t)occ > pk)
         pk = (int32_t)occ;
 }
 

@@ -225,6 +225,25 @@ def test_long_phases_cross_many_windows(K):
     assert_same(got, want)
 
 
+def test_long_thin_phases_are_evaluated_run_by_run(K):
+    # more than 64 jobs per phase, long slices and a parallelism of a handful: far more rounds
+    # than runs in flight; such phases are evaluated from the runs, not from the rounds
+    rng = np.random.default_rng(78)
+    I, n = 3, 230
+    o = rng.integers(1, 30000, (I, n)).astype(np.int32)
+    o[1, :150] = rng.integers(1, 40, 150)                      # short classes with many jobs too
+    s = rng.integers(0, 3000, (I, n)).astype(np.int32)
+    M = 60000
+    pts = [(1, 0, 2, 0), (1, 1, 3, 0), (5, 0, 5, 1), (1, 1, 2, 1), (1, 0, 0, 0), (4096, 0, 1, 0), (4096, 1, 4, 1)]
+    assert_same(run_gba(K, o, s, M, pts), O.gba_simulate_batch(o, s, M, pts))
+    e = np.clip(np.rint(o * np.exp(rng.normal(0, 0.5, o.shape))), 1, 30000).astype(np.int32)
+    assert_same(run_gba(K, o, 100, M, pts[:4], e), O.gba_simulate_batch(o, 100, M, pts[:4], e))
+    tau, k, sc = [20000, 30000, 7, 1000], [3, 1, 2, 6], [0, 1, 0, 1]
+    got = host(K.schedule_eval(dev(o), dev(s), M, tau, k, sc))
+    want = O.schedule_eval_batch(o, s, M, list(zip(tau, k, sc)))
+    assert_same(got, want, ("peak", "feasible", "flow", "job_steps", "n_completed"))
+
+
 def test_degenerate_inputs(K):
     # all jobs identical and of length one; one job; budget that admits one job at a time
     o = np.ones((3, 130), np.int32)
