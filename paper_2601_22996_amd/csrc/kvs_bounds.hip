@@ -11,6 +11,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <type_traits>
+
 #include "kvs_math.h"
 #include "kvsched.h"
 
@@ -358,7 +360,6 @@ __global__ __launch_bounds__(T) void kvs_bounds_kernel(BJobs J, BPoints P, int64
 /* ---- best list schedule over all orders ---- */
 
 constexpr int kPermT = 256;          /* threads per workgroup                  */
-constexpr uint32_t kPermPer = 32;    /* orders per thread                      */
 constexpr int kPN = KVS_MAX_PERM_JOBS;
 constexpr uint64_t kPermRounds = KVS_MAX_PERM_ROUNDS; /* largest sum of lengths of an instance */
 
@@ -378,92 +379,154 @@ __global__ void kvs_opt_init_kernel(BJobs J, int64_t *best)
 }
 
 /*
- * Flow time of the list schedule for order number idx in the factorial number
- * system (digit j picks among the n - j jobs not yet placed).  The jobs
- * already placed all start at or before the candidate start S, so from S on
- * the placed load only falls when one of them ends and rises by one per job
- * and round in between: the new run fits iff it fits in its own last round
- * and in the last round of every placed run that ends inside it.  When it
- * does not fit because some round t is over the budget by x, every start
- * before min(S + x, t + 1) still has round t inside the run and still over
- * the budget, so the search jumps there instead of trying them.
+ * Earliest start, not before `prev`, of a run of length o on top of the J runs already placed
+ * (starts S_of[0..J), ends E_of[0..J), all started at or before prev).  From the candidate
+ * start S on, the placed load only falls when one of them ends and rises by one per job and
+ * round in between: the new run fits iff it fits in its own last round and in the last round
+ * of every placed run that ends inside it.  When some round t is over the budget by x, every
+ * start before min(S + x, t + 1) still has round t inside the run and still over the budget,
+ * so the search jumps there instead of trying them.
  */
-__host__ __device__ inline int64_t list_schedule_flow(uint32_t idx, int n, const uint32_t *len,
-                                                      int64_t s1, int64_t M)
+template <int J>
+__host__ __device__ inline int64_t earliest_start(const int64_t *S_of, const int64_t *E_of, int64_t o,
+                                                   int64_t prev, int64_t s1, int64_t M)
 {
-    uint64_t avail = 0x9876543210ull; /* job ids not yet placed, 4 bits each */
-    int64_t S_of[kPN], E_of[kPN];     /* start and end (exclusive) of the placed runs */
-    int64_t prev = 0, flow = 0;
+    int64_t S = prev;
+    for (;;) {
+        const int64_t E = S + o;
+        int64_t jump = 0;
 #pragma unroll
-    for (int j = 0; j < kPN; j++) {
-        if (j < n) {
-            const uint32_t radix = (uint32_t)(n - j);
-            const uint32_t d = idx % radix;
-            idx /= radix;
-            const uint32_t id = (uint32_t)(avail >> (4 * d)) & 15u;
-            const uint64_t low = avail & ((1ull << (4 * d)) - 1ull);
-            avail = low | ((avail >> (4 * d + 4)) << (4 * d));
-            const int64_t o = len[id];
-            int64_t S = prev;
-            for (;;) {
-                const int64_t E = S + o;
-                int64_t jump = 0;
-                /* rounds to test: E - 1 and E_i - 1 for placed runs with S < E_i < E */
+        for (int c = 0; c <= J; c++) {
+            int64_t t;
+            if (c == J)
+                t = E - 1;
+            else if (E_of[c] > S && E_of[c] < E)
+                t = E_of[c] - 1;
+            else
+                continue;
+            int64_t occ = s1 + (t - S);
 #pragma unroll
-                for (int c = 0; c <= kPN; c++) {
-                    int64_t t;
-                    if (c == kPN)
-                        t = E - 1;
-                    else if (c < j && E_of[c] > S && E_of[c] < E)
-                        t = E_of[c] - 1;
-                    else
-                        continue;
-                    int64_t occ = s1 + (t - S);
-#pragma unroll
-                    for (int i = 0; i < kPN; i++)
-                        if (i < j && E_of[i] > t) /* started at or before S <= t */
-                            occ += s1 + (t - S_of[i]);
-                    if (occ > M) {
-                        const int64_t by = occ - M < t + 1 - S ? occ - M : t + 1 - S;
-                        jump = by > jump ? by : jump;
-                    }
-                }
-                if (jump == 0)
-                    break;
-                S += jump;
+            for (int i = 0; i < J; i++)
+                if (E_of[i] > t) /* started at or before S <= t */
+                    occ += s1 + (t - S_of[i]);
+            if (occ > M) {
+                const int64_t by = occ - M < t + 1 - S ? occ - M : t + 1 - S;
+                jump = by > jump ? by : jump;
             }
-            S_of[j] = S;
-            E_of[j] = S + o;
-            prev = S;
-            flow += S + o;
         }
+        if (jump == 0)
+            return S;
+        S += jump;
     }
-    return flow;
+}
+
+/* Takes the c-th of the job ids packed four bits each into `avail` and closes the gap. */
+__host__ __device__ inline uint32_t take_job(uint64_t &avail, uint32_t c)
+{
+    const uint32_t id = (uint32_t)(avail >> (4 * c)) & 15u;
+    const uint64_t low = avail & ((1ull << (4 * c)) - 1ull);
+    avail = low | ((avail >> (4 * c + 4)) << (4 * c));
+    return id;
 }
 
 /*
- * Workgroup (instance, chunk): every thread evaluates kPermPer orders and the
- * minimum goes to best[instance] with one atomic per wavefront.
+ * All orders of the jobs still in `avail` behind the J runs already placed, depth first: an
+ * order's list schedule shares the placement of every prefix with the orders that begin alike,
+ * so a prefix is placed once for all of them.  Keeps the smallest flow time in `best`.
  */
-__global__ __launch_bounds__(kPermT) void kvs_opt_perm_kernel(BJobs J, int64_t *best,
-                                                               uint32_t n_orders, uint32_t chunks)
+template <int N, int J>
+__host__ __device__ inline void orders_below(uint64_t avail, int64_t *S_of, int64_t *E_of, int64_t prev,
+                                             int64_t flow, const uint32_t *len, int64_t s1, int64_t M,
+                                             int64_t &best)
+{
+    if constexpr (J == N) {
+        best = flow < best ? flow : best;
+    } else {
+        for (uint32_t c = 0; c < (uint32_t)(N - J); c++) {
+            uint64_t rest = avail;
+            const int64_t o = len[take_job(rest, c)];
+            const int64_t S = earliest_start<J>(S_of, E_of, o, prev, s1, M);
+            S_of[J] = S;
+            E_of[J] = S + o;
+            orders_below<N, J + 1>(rest, S_of, E_of, S, flow + S + o, len, s1, M, best);
+        }
+    }
+}
+
+constexpr int kPermTail = 4; /* the last jobs of an order are enumerated by one thread */
+
+template <int N> struct PermShape {
+    static constexpr int D = N < kPermTail ? N : kPermTail; /* jobs in a thread's subtree   */
+    static constexpr int P = N - D;                         /* jobs in the prefix that names it */
+};
+
+/*
+ * Work unit `unit` of an instance of N jobs: the prefix of N - D jobs it names in the factorial
+ * number system (digit j picks among the N - j jobs not yet placed) is placed, then all D!
+ * orders of the rest are evaluated.  Returns the smallest flow time among them.
+ */
+template <int N>
+__host__ __device__ inline int64_t best_of_unit(uint32_t unit, const uint32_t *len, int64_t s1, int64_t M)
+{
+    constexpr int P = PermShape<N>::P;
+    uint64_t avail = 0x9876543210ull;
+    int64_t S_of[N], E_of[N];
+    int64_t prev = 0, flow = 0;
+    auto place = [&](auto jc) {
+        constexpr int J = decltype(jc)::value;
+        const uint32_t radix = (uint32_t)(N - J);
+        const uint32_t d = unit % radix;
+        unit /= radix;
+        const int64_t o = len[take_job(avail, d)];
+        const int64_t S = earliest_start<J>(S_of, E_of, o, prev, s1, M);
+        S_of[J] = S;
+        E_of[J] = S + o;
+        prev = S;
+        flow += S + o;
+    };
+    /* P <= 6 prefix positions, each with its own compile-time count of placed runs */
+    if constexpr (P > 0) place(std::integral_constant<int, 0>{});
+    if constexpr (P > 1) place(std::integral_constant<int, 1>{});
+    if constexpr (P > 2) place(std::integral_constant<int, 2>{});
+    if constexpr (P > 3) place(std::integral_constant<int, 3>{});
+    if constexpr (P > 4) place(std::integral_constant<int, 4>{});
+    if constexpr (P > 5) place(std::integral_constant<int, 5>{});
+    static_assert(P <= 6, "prefix positions");
+    int64_t best = INT64_MAX;
+    orders_below<N, P>(avail, S_of, E_of, prev, flow, len, s1, M, best);
+    return best;
+}
+
+/* number of work units of an instance of n jobs: n! / D! */
+__host__ __device__ inline uint32_t perm_units(int n)
+{
+    const int d = n < kPermTail ? n : kPermTail;
+    uint32_t u = 1;
+    for (int j = d + 1; j <= n; j++)
+        u *= (uint32_t)j;
+    return u;
+}
+
+/*
+ * Workgroup (instance, chunk): every thread evaluates one work unit and the minimum goes to
+ * best[instance] with one atomic per wavefront.
+ */
+template <int N>
+__global__ __launch_bounds__(kPermT) void kvs_opt_perm_kernel(BJobs J, int64_t *best, uint32_t n_units,
+                                                               uint32_t chunks)
 {
     const uint32_t inst = blockIdx.x / chunks, chunk = blockIdx.x % chunks;
-    const int n = J.n_jobs;
     __shared__ uint32_t len[kPN];
-    if (threadIdx.x < (uint32_t)n)
-        len[threadIdx.x] = (uint32_t)J.o[(size_t)inst * n + threadIdx.x];
+    if (threadIdx.x < (uint32_t)N)
+        len[threadIdx.x] = (uint32_t)J.o[(size_t)inst * N + threadIdx.x];
     __syncthreads();
     if (best[inst] < 0) /* invalid or too long: reported by the first kernel */
         return;
     const int64_t s1 = (int64_t)J.s_scalar + 1, M = (int64_t)J.M;
-
+    const uint32_t unit = chunk * kPermT + threadIdx.x;
     int64_t mine = INT64_MAX;
-    const uint32_t first = (chunk * kPermT + threadIdx.x) * kPermPer;
-    for (uint32_t c = 0; c < kPermPer && first + c < n_orders; c++) {
-        const int64_t flow = list_schedule_flow(first + c, n, len, s1, M);
-        mine = flow < mine ? flow : mine;
-    }
+    if (unit < n_units)
+        mine = best_of_unit<N>(unit, len, s1, M);
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
         const int64_t w = __shfl_xor(mine, d, kWave);
@@ -471,6 +534,31 @@ __global__ __launch_bounds__(kPermT) void kvs_opt_perm_kernel(BJobs J, int64_t *
     }
     if (threadIdx.x % kWave == 0 && mine != INT64_MAX)
         atomicMin(reinterpret_cast<long long *>(best + inst), (long long)mine);
+}
+
+template <int N>
+void launch_opt_perm(const BJobs &J, int64_t *best, uint32_t n_units, uint32_t chunks, hipStream_t st)
+{
+    hipLaunchKernelGGL(kvs_opt_perm_kernel<N>, dim3(chunks * (uint32_t)J.n_inst), dim3(kPermT), 0, st, J,
+                       best, n_units, chunks);
+}
+
+/* smallest flow time of one work unit, on the host (tests) */
+int64_t host_best_of_unit(int n, uint32_t unit, const uint32_t *len, int64_t s1, int64_t M)
+{
+    switch (n) {
+    case 1: return best_of_unit<1>(unit, len, s1, M);
+    case 2: return best_of_unit<2>(unit, len, s1, M);
+    case 3: return best_of_unit<3>(unit, len, s1, M);
+    case 4: return best_of_unit<4>(unit, len, s1, M);
+    case 5: return best_of_unit<5>(unit, len, s1, M);
+    case 6: return best_of_unit<6>(unit, len, s1, M);
+    case 7: return best_of_unit<7>(unit, len, s1, M);
+    case 8: return best_of_unit<8>(unit, len, s1, M);
+    case 9: return best_of_unit<9>(unit, len, s1, M);
+    case 10: return best_of_unit<10>(unit, len, s1, M);
+    default: return -1;
+    }
 }
 
 int32_t check_bound_jobs(const kvs_jobs_t *jobs)
@@ -567,33 +655,43 @@ int32_t kvs_opt_perm(const kvs_jobs_t *jobs, int64_t *best_flow, void *stream)
         return KVS_OK;
     if (!best_flow)
         return KVS_EINVAL;
-    uint32_t n_orders = 1;
-    for (int j = 2; j <= jobs->n_jobs; j++)
-        n_orders *= (uint32_t)j;
-    const uint32_t per_wg = kPermT * kPermPer;
-    const uint32_t chunks = (n_orders + per_wg - 1) / per_wg;
+    const uint32_t n_units = perm_units(jobs->n_jobs);
+    const uint32_t chunks = (n_units + kPermT - 1) / kPermT;
     if ((uint64_t)chunks * (uint64_t)jobs->n_instances > 0x7fffffffull)
         return KVS_ELIMIT;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const BJobs J = to_bjobs(jobs);
     hipLaunchKernelGGL(kvs_opt_init_kernel, dim3((uint32_t)(jobs->n_instances + 255) / 256), dim3(256),
                        0, st, J, best_flow);
-    hipLaunchKernelGGL(kvs_opt_perm_kernel, dim3(chunks * (uint32_t)jobs->n_instances), dim3(kPermT),
-                       0, st, J, best_flow, n_orders, chunks);
+    switch (jobs->n_jobs) {
+    case 1: launch_opt_perm<1>(J, best_flow, n_units, chunks, st); break;
+    case 2: launch_opt_perm<2>(J, best_flow, n_units, chunks, st); break;
+    case 3: launch_opt_perm<3>(J, best_flow, n_units, chunks, st); break;
+    case 4: launch_opt_perm<4>(J, best_flow, n_units, chunks, st); break;
+    case 5: launch_opt_perm<5>(J, best_flow, n_units, chunks, st); break;
+    case 6: launch_opt_perm<6>(J, best_flow, n_units, chunks, st); break;
+    case 7: launch_opt_perm<7>(J, best_flow, n_units, chunks, st); break;
+    case 8: launch_opt_perm<8>(J, best_flow, n_units, chunks, st); break;
+    case 9: launch_opt_perm<9>(J, best_flow, n_units, chunks, st); break;
+    default: launch_opt_perm<10>(J, best_flow, n_units, chunks, st); break;
+    }
     return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
 }
 
 /* Host-side access to the kernels' arithmetic, for tests without a GPU. */
 uint64_t kvs_host_floor_sum(uint64_t n, uint64_t k, uint64_t tau) { return kvs_floor_sum(n, k, tau); }
 
-int64_t kvs_host_list_schedule_flow(uint32_t order, int32_t n, const int32_t *o, int64_t s, int64_t M)
+/* Smallest flow time of work unit `unit` (of kvs_host_perm_units(n)) of one instance. */
+int64_t kvs_host_best_of_unit(uint32_t unit, int32_t n, const int32_t *o, int64_t s, int64_t M)
 {
     uint32_t len[kPN] = {0};
-    if (n < 1 || n > kPN)
+    if (n < 1 || n > kPN || unit >= perm_units(n))
         return -1;
     for (int j = 0; j < n; j++)
         len[j] = (uint32_t)o[j];
-    return list_schedule_flow(order, n, len, s + 1, M);
+    return host_best_of_unit(n, unit, len, s + 1, M);
 }
+
+uint32_t kvs_host_perm_units(int32_t n) { return (n < 1 || n > kPN) ? 0u : perm_units(n); }
 
 } // extern "C"

@@ -80,8 +80,10 @@ def lib():
         L.kvs_host_kstar.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
         L.kvs_host_floor_sum.restype = C.c_uint64
         L.kvs_host_floor_sum.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
-        L.kvs_host_list_schedule_flow.restype = C.c_int64
-        L.kvs_host_list_schedule_flow.argtypes = [C.c_uint32, i32, C.POINTER(i32), C.c_int64, C.c_int64]
+        L.kvs_host_best_of_unit.restype = C.c_int64
+        L.kvs_host_best_of_unit.argtypes = [C.c_uint32, i32, C.POINTER(i32), C.c_int64, C.c_int64]
+        L.kvs_host_perm_units.restype = C.c_uint32
+        L.kvs_host_perm_units.argtypes = [i32]
         _lib = L
     return _lib
 

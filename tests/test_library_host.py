@@ -157,33 +157,43 @@ def test_floor_sum_matches_the_plain_sum(L):
     assert L.kvs_host_floor_sum(n, 7, tau) == sum(i * tau // 7 for i in range(n))
 
 
-def test_list_schedule_of_every_order_against_the_oracle(L):
-    """The kernel's evaluation of one order (event rounds only, jumps in the search for the
-    start) run on the host for every order number: the minimum is the oracle's, and each
-    order number decodes to a different order."""
+def test_list_schedules_of_every_order_against_the_oracle(L):
+    """The kernel's enumeration (a work unit = a prefix of the order, all orders of the last
+    four jobs below it depth first; event rounds only, jumps in the search for a start) run on
+    the host for every work unit: the minimum over the units is the oracle's."""
+    import math
     import numpy as np
     import oracle as O
-    L.kvs_host_list_schedule_flow.restype = C.c_int64
-    L.kvs_host_list_schedule_flow.argtypes = [C.c_uint32, C.c_int32, C.POINTER(C.c_int32), C.c_int64, C.c_int64]
+    L.kvs_host_best_of_unit.restype = C.c_int64
+    L.kvs_host_best_of_unit.argtypes = [C.c_uint32, C.c_int32, C.POINTER(C.c_int32), C.c_int64, C.c_int64]
+    L.kvs_host_perm_units.restype = C.c_uint32
+    L.kvs_host_perm_units.argtypes = [C.c_int32]
+    for n in range(1, 11):
+        assert L.kvs_host_perm_units(n) == math.factorial(n) // math.factorial(min(n, 4))
     rng = np.random.default_rng(8)
-    fact = [1, 1, 2, 6, 24, 120, 720]
-    for case in range(40):
-        n = int(rng.integers(1, 7))
+    for case in range(48):
+        n = int(rng.integers(1, 8))
         o = rng.integers(1, 12, n).astype(np.int32)
         s = int(rng.integers(0, 5))
         M = int(rng.integers(s + 12, 45)) if case % 4 else s + int(o.max())   # no two jobs overlap
         ptr = o.ctypes.data_as(C.POINTER(C.c_int32))
-        flows = [L.kvs_host_list_schedule_flow(i, n, ptr, s, M) for i in range(fact[n])]
-        assert min(flows) == O.opt_perm(o, s, M), (o, s, M)
-        # identity order = order number 0: compare with the oracle's stepping of that one order
-        assert min(flows) >= int(o.sum())
-    # by hand: two jobs that cannot overlap, either order: 2 + 5 or 3 + 5
+        units = L.kvs_host_perm_units(n)
+        best = min(L.kvs_host_best_of_unit(u, n, ptr, s, M) for u in range(units))
+        assert best == O.opt_perm(o, s, M), (o, s, M)
+        assert L.kvs_host_best_of_unit(units, n, ptr, s, M) == -1                # no such unit
+    # by hand: two jobs that cannot overlap: shortest first, 2 + 5
     o = np.array([3, 2], np.int32)
-    ptr = o.ctypes.data_as(C.POINTER(C.c_int32))
-    assert sorted(L.kvs_host_list_schedule_flow(i, 2, ptr, 2, 5) for i in range(2)) == [7, 8]
-    # o = 2, 2, s = 0, M = 3: second job starts one round later
+    assert L.kvs_host_best_of_unit(0, 2, o.ctypes.data_as(C.POINTER(C.c_int32)), 2, 5) == 7
+    # o = 2, 2, s = 0, M = 3: the second job starts one round later
     o = np.array([2, 2], np.int32)
-    assert L.kvs_host_list_schedule_flow(0, 2, o.ctypes.data_as(C.POINTER(C.c_int32)), 0, 3) == 5
+    assert L.kvs_host_best_of_unit(0, 2, o.ctypes.data_as(C.POINTER(C.c_int32)), 0, 3) == 5
+    # five jobs: unit u fixes the first job (the u-th of the input) and enumerates the rest below
+    # it.  No two jobs can overlap (s + 1 = 5 each, M = 8), so the best order is shortest first:
+    # 1 + 2 + 3 + 4 + 7 when a unit job leads, 3 + 4 + 5 + 6 + 7 when the long one does
+    o = np.array([3, 1, 1, 1, 1], np.int32)
+    ptr = o.ctypes.data_as(C.POINTER(C.c_int32))
+    per_first = [L.kvs_host_best_of_unit(u, 5, ptr, 4, 8) for u in range(5)]
+    assert per_first == [25, 17, 17, 17, 17] and O.opt_perm(o, 4, 8) == 17
 
 
 def test_bounds_argument_checks(L):
