@@ -58,9 +58,8 @@ __device__ __forceinline__ uint64_t wave_max64(uint64_t v)
 }
 
 
-/* ---- bitonic sort of up to 16 keys per thread, in LDS ---- */
+/* ---- bitonic sort in LDS, 16 keys per thread and pass ---- */
 
-constexpr int kPerThread = 16; /* keys a thread holds; a workgroup of T threads sorts up to 16 T */
 
 /* One unused word after every 16 keys: a thread that reads 16 consecutive keys and its
  * neighbours then fall into different banks. */
@@ -81,16 +80,20 @@ template <typename KT> __device__ __forceinline__ void order_pair(KT &a, KT &b)
  * index); descending blocks are merged ascending on the complemented keys.
  */
 template <typename KT, int R, int T>
-__device__ __forceinline__ void merge_stages(KT *key, uint32_t n_pad, uint32_t k, uint32_t b_low,
-                                             uint32_t tid)
+__device__ __forceinline__ void merge_stages(KT *key, uint32_t n_pad, KT *key2, uint32_t n_pad2, uint32_t k,
+                                             uint32_t b_low, uint32_t tid)
 {
-    for (uint32_t g = tid; g < (n_pad >> R); g += T) {
+    /* the groups of the first run, then (while its merges are this long) those of the second */
+    const uint32_t g1 = n_pad >> R, g2 = (k <= n_pad2) ? (n_pad2 >> R) : 0u;
+    for (uint32_t gg = tid; gg < g1 + g2; gg += T) {
+        KT *run = gg < g1 ? key : key2;
+        const uint32_t g = gg < g1 ? gg : gg - g1;
         const uint32_t base = ((g >> b_low) << (b_low + R)) | (g & ((1u << b_low) - 1u));
         const KT flip = (base & k) ? ~(KT)0 : (KT)0;
         KT v[1 << R];
 #pragma unroll
         for (int e = 0; e < (1 << R); e++)
-            v[e] = key[slot_of(base + ((uint32_t)e << b_low))] ^ flip;
+            v[e] = run[slot_of(base + ((uint32_t)e << b_low))] ^ flip;
 #pragma unroll
         for (int bit = R - 1; bit >= 0; bit--)
 #pragma unroll
@@ -99,23 +102,26 @@ __device__ __forceinline__ void merge_stages(KT *key, uint32_t n_pad, uint32_t k
                     order_pair(v[e], v[e | (1 << bit)]);
 #pragma unroll
         for (int e = 0; e < (1 << R); e++)
-            key[slot_of(base + ((uint32_t)e << b_low))] = v[e] ^ flip;
+            run[slot_of(base + ((uint32_t)e << b_low))] = v[e] ^ flip;
     }
     __syncthreads();
 }
 
-/* Sorts key[slot_of(0 .. n_pad-1)] ascending; n_pad a power of two, 16 <= n_pad <= 16 T.
+/* Sorts two runs ascending in the same sequence of passes: key[slot_of(0 .. n_pad-1)] and
+ * key2[slot_of(0 .. n_pad2-1)], n_pad >= n_pad2, each a power of two >= 16 (n_pad2 may be 0).
  * Every thread of the workgroup must call it. */
 template <typename KT, int T>
-__device__ void bitonic_sort(KT *key, uint32_t n_pad, uint32_t tid)
+__device__ void bitonic_sort(KT *key, uint32_t n_pad, KT *key2, uint32_t n_pad2, uint32_t tid)
 {
     /* blocks of 16 consecutive keys: the merges k = 2, 4, 8, 16 entirely in registers */
-    for (uint32_t g = tid; g < n_pad / 16; g += T) {
-        const uint32_t base = g * 16;
+    const uint32_t g1 = n_pad / 16, g2 = n_pad2 / 16;
+    for (uint32_t gg = tid; gg < g1 + g2; gg += T) {
+        KT *run = gg < g1 ? key : key2;
+        const uint32_t base = (gg < g1 ? gg : gg - g1) * 16;
         KT v[16];
 #pragma unroll
         for (int e = 0; e < 16; e++)
-            v[e] = key[slot_of(base + e)];
+            v[e] = run[slot_of(base + e)];
 #pragma unroll
         for (int k = 2; k <= 8; k <<= 1)
 #pragma unroll
@@ -128,7 +134,9 @@ __device__ void bitonic_sort(KT *key, uint32_t n_pad, uint32_t tid)
                         else
                             order_pair(v[e], v[e | j]);
                     }
-        const KT flip = (base & 16u) ? ~(KT)0 : (KT)0;
+        /* the run of 16 is sorted upwards on its own, and in a longer run by bit 4 of its place */
+        const uint32_t len = gg < g1 ? n_pad : n_pad2;
+        const KT flip = (len > 16u && (base & 16u)) ? ~(KT)0 : (KT)0;
 #pragma unroll
         for (int j = 8; j > 0; j >>= 1)
 #pragma unroll
@@ -141,48 +149,125 @@ __device__ void bitonic_sort(KT *key, uint32_t n_pad, uint32_t tid)
                 }
 #pragma unroll
         for (int e = 0; e < 16; e++)
-            key[slot_of(base + e)] = v[e];
+            run[slot_of(base + e)] = v[e];
     }
     __syncthreads();
     for (uint32_t m = 5; (1u << m) <= n_pad; m++) {
         const uint32_t k = 1u << m;
         uint32_t b = m; /* stages of the bits b-1 .. 0 are still to do */
         switch (m % 4) {
-        case 1: merge_stages<KT, 1, T>(key, n_pad, k, b - 1, tid); b -= 1; break;
-        case 2: merge_stages<KT, 2, T>(key, n_pad, k, b - 2, tid); b -= 2; break;
-        case 3: merge_stages<KT, 3, T>(key, n_pad, k, b - 3, tid); b -= 3; break;
+        case 1: merge_stages<KT, 1, T>(key, n_pad, key2, n_pad2, k, b - 1, tid); b -= 1; break;
+        case 2: merge_stages<KT, 2, T>(key, n_pad, key2, n_pad2, k, b - 2, tid); b -= 2; break;
+        case 3: merge_stages<KT, 3, T>(key, n_pad, key2, n_pad2, k, b - 3, tid); b -= 3; break;
         default: break;
         }
         for (; b >= 4; b -= 4)
-            merge_stages<KT, 4, T>(key, n_pad, k, b - 4, tid);
+            merge_stages<KT, 4, T>(key, n_pad, key2, n_pad2, k, b - 4, tid);
     }
 }
 
+/* The keys are sorted as one or two runs of power-of-two length: all of them in one run when
+ * n is close below a power of two, else the first 2^floor(log2 n) in run A and the rest, padded
+ * to a power of two, in run B (10 000 keys: 8192 + 2048 instead of 16 384). */
+struct TwoRuns {
+    uint32_t a, b; /* lengths of the runs, b == 0: one run */
+};
+
+__host__ __device__ inline TwoRuns split_runs(uint32_t n)
+{
+    TwoRuns r;
+    uint32_t a = 16;
+    while (a * 2u <= n)
+        a *= 2u;
+    if (n <= a) { /* n <= 16, or a power of two */
+        r.a = a;
+        r.b = 0;
+        return r;
+    }
+    uint32_t b = 16;
+    while (b < n - a)
+        b *= 2u;
+    if (b == a) {
+        r.a = 2u * a;
+        r.b = 0;
+    } else {
+        r.a = a;
+        r.b = b;
+    }
+    return r;
+}
+
+/* number of keys below x (or not above it, when `or_equal`) in a sorted run of `len` keys */
+template <typename KT>
+__device__ __forceinline__ uint32_t rank_in_run(const KT *run, uint32_t len, KT x, bool or_equal)
+{
+    uint32_t lo = 0, hi = len;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        const KT v = run[slot_of(mid)];
+        if (v < x || (or_equal && v == x))
+            lo = mid + 1u;
+        else
+            hi = mid;
+    }
+    return lo;
+}
+
 /*
- * One workgroup per instance (T threads, n_jobs <= 16 T).
- *
- * LDS: the jobs as (o, s) pairs, later overwritten by their areas (32-bit
- * keys when the largest area allows, else 64-bit) and sorted; per wavefront
- * one histogram of the levels of the current base.
- *
- * 1. load and check the jobs;
- * 2. per distinct base: count the jobs and keep the largest prompt per level
- *    g (smallest g with base * 2^g >= o).  The class of a job at the point
- *    base * 2^m is max(0, g - m), so a point's class table is the level table
- *    with the levels 0..m merged.  32 consecutive lanes take the classes of
- *    one point: each computes k_p, Q_p and floor(n_p tau_p / k_p) + tau_p, a
- *    prefix sum over the lanes gives S_p, a sum n_p S_p + Q_p the bound
- *    (Step 3 of the analysis of GBA);
- * 3. areas in place of the pairs, bitonic sort (16 keys per thread, up to four
- *    stages per pass over LDS), sum of (n - j) * area_j over
- *    the ascending sequence j = 0 .. n-1 (Step 1, proof of the lower bound).
+ * Sorts the n keys laid out as split_runs(n) says (run A at key[slot_of(0..)), run B behind it,
+ * padded with the largest value) and returns this thread's share of sum_j (n - j) * key_(j) over
+ * the ascending sequence j = 0 .. n-1.  A key's place in that sequence is its place in its own
+ * run plus the number of keys of the other run in front of it (equal keys: run A first).
  */
-template <int T>
-__global__ __launch_bounds__(T) void kvs_bounds_kernel(BJobs J, BPoints P, int64_t *upper,
+template <typename KT, int T>
+__device__ uint64_t ranked_sum(KT *key, uint32_t n, TwoRuns runs, uint32_t tid)
+{
+    KT *run_b = key + slot_of(runs.a); /* runs.a is a multiple of 16 */
+    bitonic_sort<KT, T>(key, runs.a, run_b, runs.b, tid);
+    uint64_t sum = 0;
+    const uint32_t in_a = n < runs.a ? n : runs.a, in_b = n - in_a; /* real keys; padding sorts behind them */
+    for (uint32_t i = tid; i < in_a; i += T) {
+        const KT x = key[slot_of(i)];
+        const uint32_t j = i + (runs.b ? rank_in_run(run_b, in_b, x, false) : 0u);
+        sum += (uint64_t)(n - j) * x;
+    }
+    for (uint32_t i = tid; i < in_b; i += T) {
+        const KT x = run_b[slot_of(i)];
+        const uint32_t j = i + rank_in_run(key, in_a, x, true);
+        sum += (uint64_t)(n - j) * x;
+    }
+    return sum;
+}
+
+constexpr int64_t kAreaPending = INT64_MIN; /* internal: areas too wide for 32-bit keys, left to the second launch */
+
+/*
+ * One workgroup per instance (T threads, n_jobs <= 16 T).  LDS holds only the sort keys --
+ * 32-bit in the first launch
+ * (WIDE = false), which leaves an instance whose largest area needs more to the second launch
+ * with 64-bit keys (WIDE = true, twice the LDS, one workgroup per compute unit instead of two)
+ * -- and per wavefront one histogram of the levels of the current base.
+ *
+ * 1. load and check the jobs, find the largest area; the level histogram of the first base is
+ *    counted on the way;
+ * 2. UpperGBA (first launch only): per distinct base the jobs are counted and the largest
+ *    prompt kept per level g (smallest g with base * 2^g >= o; further bases read the jobs
+ *    again, from cache).  The class of a job at the point base * 2^m is max(0, g - m), so a
+ *    point's class table is the level table with the levels 0..m merged.  32 consecutive lanes
+ *    take the classes of one point: each computes k_p, Q_p and floor(n_p tau_p / k_p) + tau_p,
+ *    a prefix sum over the lanes gives S_p, a sum n_p S_p + Q_p the bound (Step 3 of the
+ *    analysis of GBA);
+ * 3. the areas (jobs read again, from cache) sorted as one or two runs (bitonic, 16 keys per thread, up to four stages per
+ *    pass over LDS), sum of (n - j) * area_j over the ascending sequence j = 0 .. n-1 (Step 1,
+ *    proof of the lower bound).
+ */
+template <int T, bool WIDE>
+__global__ __launch_bounds__(T, (T == 1024 && !WIDE) ? 8 : 1) void kvs_bounds_kernel(BJobs J, BPoints P, int64_t *upper,
                                                         int64_t *area_num)
 {
+    using KT = typename std::conditional<WIDE, uint64_t, uint32_t>::type;
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    uint64_t *key = reinterpret_cast<uint64_t *>(lds_raw); /* n_pad entries */
+    KT *key = reinterpret_cast<KT *>(lds_raw);
     constexpr int NW = T / kWave;
     __shared__ uint32_t hist[NW][kLevels];
     __shared__ uint32_t smax_lv[kLevels];
@@ -193,26 +278,53 @@ __global__ __launch_bounds__(T) void kvs_bounds_kernel(BJobs J, BPoints P, int64
     const uint32_t inst = blockIdx.x, tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const uint32_t n = (uint32_t)J.n_jobs;
     const size_t row = (size_t)inst * n;
-    uint32_t n_pad = 16;
-    while (n_pad < n)
-        n_pad <<= 1;
+    if (WIDE && area_num[inst] != kAreaPending)
+        return; /* the first launch has finished this instance */
+    const bool want_upper = !WIDE && upper && P.n_pts > 0;
+
+    auto clear_hist = [&]() {
+        for (uint32_t i = tid; i < NW * kLevels; i += T)
+            (&hist[0][0])[i] = 0;
+        if (tid < kLevels)
+            smax_lv[tid] = 0;
+    };
+    /* a job as it counts: an invalid one marks the instance and is replaced by (o, s) = (1, 0) */
+    auto read_job = [&](uint32_t i, uint32_t &o, uint32_t &s) -> bool {
+        const int32_t oi = J.o[row + i];
+        const int64_t si = J.s ? (int64_t)J.s[row + i] : (int64_t)J.s_scalar;
+        const bool ok = !(oi < 1 || si < 0 || (uint32_t)oi > kLenMax || si > (int64_t)kLenMax ||
+                          (uint64_t)si + (uint64_t)oi > J.M);
+        o = ok ? (uint32_t)oi : 1u;
+        s = ok ? (uint32_t)si : 0u;
+        return ok;
+    };
+    auto count_level = [&](uint32_t o, uint32_t s, uint32_t base, uint32_t lg) {
+        const uint32_t g = kvs_class_index(o, base, lg);
+        atomicAdd(&hist[wave][g], 1u);
+        if (s > smax_lv[g])
+            atomicMax(&smax_lv[g], s);
+    };
 
     if (tid == 0)
         bad = 0;
+    if (want_upper)
+        clear_hist();
     __syncthreads();
 
     /* 1. load */
+    auto area_of = [](uint32_t o, uint32_t s) { /* Area(o, s) < 2^61 */
+        return (uint64_t)s * o + (uint64_t)o * (o + 1u) / 2u;
+    };
+    uint64_t amax = 0;
     uint32_t my_bad = 0;
     for (uint32_t i = tid; i < n; i += T) {
-        const int32_t o = J.o[row + i];
-        const int64_t s = J.s ? (int64_t)J.s[row + i] : (int64_t)J.s_scalar;
-        if (o < 1 || s < 0 || (uint32_t)o > kLenMax || s > (int64_t)kLenMax ||
-            (uint64_t)s + (uint64_t)o > J.M) {
+        uint32_t o, s;
+        if (!read_job(i, o, s))
             my_bad = 1;
-            key[i] = 1; /* o = 1, s = 0: keeps the loops below in range */
-        } else {
-            key[i] = ((uint64_t)(uint32_t)s << 32) | (uint32_t)o;
-        }
+        const uint64_t a = area_of(o, s);
+        amax = a > amax ? a : amax;
+        if (want_upper)
+            count_level(o, s, P.base[0], P.lg_base[0]);
     }
     if (my_bad)
         atomicOr(&bad, 1u);
@@ -220,23 +332,19 @@ __global__ __launch_bounds__(T) void kvs_bounds_kernel(BJobs J, BPoints P, int64
     const bool invalid = bad != 0;
 
     /* 2. class tables and UpperGBA: 32 consecutive lanes hold the 32 classes of one point */
-    if (upper && P.n_pts > 0) {
+    if (want_upper) {
         for (int b = 0; b < P.n_bases; b++) {
-            for (uint32_t i = tid; i < NW * kLevels; i += T)
-                (&hist[0][0])[i] = 0;
-            if (tid < kLevels)
-                smax_lv[tid] = 0;
-            __syncthreads();
             const uint32_t base = P.base[b], lg = P.lg_base[b];
-            for (uint32_t i = tid; i < n; i += T) {
-                const uint64_t e = key[i];
-                const uint32_t o = (uint32_t)e, s = (uint32_t)(e >> 32);
-                const uint32_t g = kvs_class_index(o, base, lg);
-                atomicAdd(&hist[wave][g], 1u);
-                if (s > smax_lv[g])
-                    atomicMax(&smax_lv[g], s);
+            if (b > 0) {
+                clear_hist();
+                __syncthreads();
+                for (uint32_t i = tid; i < n; i += T) {
+                    uint32_t o, s;
+                    read_job(i, o, s);
+                    count_level(o, s, base, lg);
+                }
+                __syncthreads();
             }
-            __syncthreads();
             if (tid < kLevels) {
                 uint32_t c = 0;
                 for (int w = 0; w < NW; w++)
@@ -297,53 +405,39 @@ __global__ __launch_bounds__(T) void kvs_bounds_kernel(BJobs J, BPoints P, int64
     if (!area_num)
         return;
 
-    /* 3. areas, sorted ascending.  A thread takes its (at most 16) jobs out of LDS first: the
-     * sorted layout overlaps the pairs. */
-    uint64_t area[kPerThread];
-    uint64_t amax = 0;
-#pragma unroll
-    for (int c = 0; c < kPerThread; c++) {
-        const uint32_t i = tid + (uint32_t)c * T;
-        area[c] = ~0ull; /* padding sorts to the end */
-        if (i < n) {
-            const uint64_t e = key[i];
-            const uint64_t o = (uint32_t)e, s = e >> 32;
-            area[c] = s * o + o * (o + 1u) / 2u; /* Area(o, s) < 2^61 */
-            amax = area[c] > amax ? area[c] : amax;
-        }
-    }
+    /* 3. areas, sorted ascending */
     amax = wave_max64(amax);
     if (lane == 0)
         red[wave] = amax;
-    __syncthreads(); /* every pair has been read */
+    __syncthreads();
     amax = 0;
     for (int w = 0; w < NW; w++)
         amax = red[w] > amax ? red[w] : amax;
-    const bool narrow = amax < 0xffffffffull; /* 32-bit keys: half the LDS traffic */
-    uint32_t *key32 = reinterpret_cast<uint32_t *>(lds_raw);
-#pragma unroll
-    for (int c = 0; c < kPerThread; c++) {
-        const uint32_t i = tid + (uint32_t)c * T;
-        if (i < n_pad) {
-            if (narrow)
-                key32[slot_of(i)] = i < n ? (uint32_t)area[c] : ~0u;
-            else
-                key[slot_of(i)] = area[c];
+    __syncthreads();
+    if (invalid) {
+        if (tid == 0)
+            area_num[inst] = -1;
+        return;
+    }
+    if (!WIDE && amax >= 0xffffffffull) { /* needs 64-bit keys (the padding takes the largest 32-bit value) */
+        if (tid == 0)
+            area_num[inst] = kAreaPending;
+        return;
+    }
+    const TwoRuns runs = split_runs(n);
+    const uint32_t b0 = slot_of(runs.a); /* where run B begins */
+    for (uint32_t i = tid; i < runs.a + runs.b; i += T) { /* the jobs again, from cache */
+        KT a = (KT) ~(KT)0; /* padding sorts to the end */
+        if (i < n) {
+            uint32_t o, s;
+            read_job(i, o, s);
+            a = (KT)area_of(o, s);
         }
+        key[i < runs.a ? slot_of(i) : b0 + slot_of(i - runs.a)] = a;
     }
     __syncthreads();
-    uint64_t sum = 0;
-    if (narrow) {
-        bitonic_sort<uint32_t, T>(key32, n_pad, tid);
-        for (uint32_t i = tid; i < n; i += T)
-            sum += (uint64_t)(n - i) * key32[slot_of(i)];
-    } else {
-        bitonic_sort<uint64_t, T>(key, n_pad, tid);
-        for (uint32_t i = tid; i < n; i += T)
-            sum += (uint64_t)(n - i) * key[slot_of(i)];
-    }
+    uint64_t sum = ranked_sum<KT, T>(key, n, runs, tid);
     sum = wave_sum64(sum);
-    __syncthreads();
     if (lane == 0)
         red[wave] = sum;
     __syncthreads();
@@ -353,7 +447,7 @@ __global__ __launch_bounds__(T) void kvs_bounds_kernel(BJobs J, BPoints P, int64
             tot += red[w];
         const uint64_t tri = (uint64_t)n * (n + 1u) / 2u;
         const bool wide = __umul64hi(tri, amax) != 0 || tri * amax >= (1ull << 63);
-        area_num[inst] = (invalid || wide) ? -1 : (int64_t)tot;
+        area_num[inst] = wide ? -1 : (int64_t)tot;
     }
 }
 
@@ -621,13 +715,13 @@ int32_t kvs_flow_bounds(const kvs_jobs_t *jobs, const int32_t *tau0, int32_t n_p
     }
     if (jobs->n_instances == 0 || (n_pts == 0 && !area_lb_num))
         return KVS_OK;
-    uint32_t n_pad = 16;
-    while (n_pad < (uint32_t)jobs->n_jobs)
-        n_pad <<= 1;
-    /* room for the (o, s) pairs and for 64-bit keys with one unused slot per 16 */
-    const size_t lds = sizeof(uint64_t) * (n_pad + n_pad / 16 + 1);
+    /* the runs of keys with one unused slot per 16: 32-bit keys in the first launch, 64-bit in
+     * the second, which takes the instances the first one left (areas of 2^32 and more) */
+    const uint32_t n = (uint32_t)jobs->n_jobs;
+    const TwoRuns runs = split_runs(n);
+    const size_t slots = (size_t)runs.a + runs.a / 16 + runs.b + runs.b / 16 + 1;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    auto launch = [&](auto kern, int threads) -> int32_t {
+    auto launch = [&](auto kern, int threads, size_t lds) -> int32_t {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return KVS_EHIP;
@@ -635,11 +729,15 @@ int32_t kvs_flow_bounds(const kvs_jobs_t *jobs, const int32_t *tau0, int32_t n_p
                            to_bjobs(jobs), P, n_pts > 0 ? upper_gba : nullptr, area_lb_num);
         return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
     };
-    /* a thread holds at most 16 keys */
-    static_assert(KVS_MAX_JOBS <= 16 * 1024, "largest instance must fit 1024 threads");
-    return n_pad > 4096   ? launch(kvs_bounds_kernel<1024>, 1024)
-           : n_pad > 1024 ? launch(kvs_bounds_kernel<256>, 256)
-                          : launch(kvs_bounds_kernel<64>, 64);
+    const size_t lds32 = sizeof(uint32_t) * slots, lds64 = sizeof(uint64_t) * slots;
+    rc = n > 4096   ? launch(kvs_bounds_kernel<1024, false>, 1024, lds32)
+         : n > 1024 ? launch(kvs_bounds_kernel<256, false>, 256, lds32)
+                    : launch(kvs_bounds_kernel<64, false>, 64, lds32);
+    if (rc != KVS_OK || !area_lb_num)
+        return rc;
+    return n > 4096   ? launch(kvs_bounds_kernel<1024, true>, 1024, lds64)
+           : n > 1024 ? launch(kvs_bounds_kernel<256, true>, 256, lds64)
+                      : launch(kvs_bounds_kernel<64, true>, 64, lds64);
 }
 
 int32_t kvs_opt_perm(const kvs_jobs_t *jobs, int64_t *best_flow, void *stream)
