@@ -264,7 +264,8 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
                 sumO += v.o; /* every job completes once; a lone invocation completes o <= tau */
             mxO = v.o > mxO ? v.o : mxO;
             mxS = v.s > mxS ? v.s : mxS;
-            mxG = v.gb > mxG ? v.gb : mxG;
+            if (!NESTED) /* only the entry format of the other instantiations asks for it */
+                mxG = v.gb > mxG ? v.gb : mxG;
             if (NESTED) /* the job as a phase entry, at its place in the input */
                 buf[i] = per_job_s ? ((v.s << 16) | (v.o & 0xffffu)) : v.o;
             atomicAdd(&myE[v.ga], 1u); /* the wavefront's own histogram */
@@ -273,9 +274,10 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
             if (per_job_s) { /* the maxima settle after a few jobs; then this only reads */
                 if (v.s > sMaxEnter[v.ga])
                     atomicMax(&sMaxEnter[v.ga], v.s);
-                for (uint32_t l = v.ga; l <= v.gb; l++)
-                    if (v.s > sMaxPart[l])
-                        atomicMax(&sMaxPart[l], v.s);
+                if (!NESTED) /* one phase per job: the levels it takes part in are the one it enters */
+                    for (uint32_t l = v.ga; l <= v.gb; l++)
+                        if (v.s > sMaxPart[l])
+                            atomicMax(&sMaxPart[l], v.s);
             }
         };
         if (J.vec4) {
@@ -444,7 +446,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
                 sl.n = enter - left;
                 sl.done = totL[lv];
                 if (per_job_s)
-                    sl.smax = sMaxPart[lv];
+                    sl.smax = NESTED ? sMaxEnter[lv] : sMaxPart[lv];
                 if (one_phase_each) { /* the multisplit keeps every level's jobs side by side */
                     for (uint32_t l = 0; l < lv; l++)
                         off += totE[l];
