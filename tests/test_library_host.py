@@ -28,6 +28,14 @@ def L():
     return lib
 
 
+def test_built_library_is_not_older_than_its_sources():
+    # the GPU tests and the benchmark load the built library as it is; a library older than the
+    # sources would test and time something else than what is committed
+    if not os.path.exists(B.LIB):
+        B.build()
+    assert not B.is_stale(), "run `python paper_2601_22996_amd/build.py`: a source is newer than the library"
+
+
 def test_exports_every_declared_symbol(L):
     header = open(os.path.join(ROOT, "include", "kvsched.h")).read()
     names = set(re.findall(r"\b(kvs_[a-z_]+)\s*\(", header))
