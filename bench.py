@@ -29,13 +29,16 @@ TRAFFIC_NOTE = os.path.join(ROOT, "profiles", "kvs_sweep_kernel_cfg5_pareto_traf
 
 
 def kernel_source_digest():
-    """sha256 over the sources the evaluation kernel is built from."""
+    """sha256 over the code of the sources the evaluation kernel is built from (comments and
+    white space do not count: they do not change the kernel)."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for rel in ("paper_2601_22996_amd/csrc/kvs_kernels.hip", "paper_2601_22996_amd/csrc/kvs_phase.h",
                 "paper_2601_22996_amd/csrc/kvs_wave.h", "paper_2601_22996_amd/csrc/kvs_math.h"):
-        with open(os.path.join(ROOT, rel), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, rel), "r") as f:
+            code = re.sub(r"/\*.*?\*/|//[^\n]*", " ", f.read(), flags=re.S)
+        h.update(" ".join(code.split()).encode())
     return h.hexdigest()
 
 

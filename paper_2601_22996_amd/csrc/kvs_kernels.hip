@@ -15,8 +15,10 @@
  * first phase and uses the levels above m unchanged.  So every level phase is
  * evaluated once per (subroutine, parallelism) variant and shared by all the
  * points, and only the merged first phases are evaluated per shift.  Jobs are
- * brought into phase order in LDS (a stable multisplit by level when every
- * job has exactly one phase, stable compaction per phase otherwise).  Inside
+ * brought into phase order in LDS: when every job has exactly one phase, a
+ * copy of the instance is cut into the phases by stable partitions inside LDS
+ * (the jobs are read from memory once); otherwise each phase is compacted
+ * from memory.  Inside
  * a phase nothing is stepped round by round: the occupancy of round t is
  *     occ(t) = A(t) + t * C(t),
  *     C(t) = number of active runs,  A(t) = sum over them of (s + 1 - start),
