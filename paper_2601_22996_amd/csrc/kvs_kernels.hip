@@ -1036,11 +1036,11 @@ int32_t run_group_lv(const JobsDev &J, const GroupArg &G, const OutsDev &out, hi
     /* Large instances: 12 wavefronts and 256-round windows keep two workgroups (24 wavefronts)
      * on a compute unit next to a 40 KB phase buffer; measured best among the shapes tried. */
     if (one_phase_each)
-        rc = !big ? launch_sweep<256, true, true, 384, LV, 16>(J, G, out, st)
+        rc = !big ? launch_sweep<256, true, true, 256, LV, 16>(J, G, out, st)
              : mid ? launch_sweep<768, true, true, 256, LV, kHoldMid>(J, G, out, st)
                    : launch_sweep<768, true, true, 256, LV, kHoldMax>(J, G, out, st);
     else
-        rc = !big ? launch_sweep<256, true, false, 384, LV, 1>(J, G, out, st)
+        rc = !big ? launch_sweep<256, true, false, 256, LV, 1>(J, G, out, st)
                   : launch_sweep<768, true, false, 256, LV, 1>(J, G, out, st);
     if (rc != KVS_OK || !J.s)
         return rc;
