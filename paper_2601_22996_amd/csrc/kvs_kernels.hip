@@ -561,42 +561,40 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
     uint32_t next_item = 0; /* slabs are dealt to the wavefronts in turn */
 
     auto eval_slot = [&](int si) {
-        const Slot sl = slot[si];
-        if (sl.n == 0 || sl.alias != (uint32_t)si)
+        const uint32_t n_runs = slot[si].n;
+        if (n_runs == 0 || slot[si].alias != (uint32_t)si)
             return;
         for (int vi = 0; vi < (int)G.n_v; vi++) {
+            /* work items of this (slot, variant): one for a phase of at most 64 runs, else its
+             * slabs (or groups of runs).  This wavefront takes every NW-th, starting where the
+             * dealing has got to, and reads the tables only if something falls to it. */
+            const uint32_t items = n_runs <= 64u ? 1u : sched[vi][si].nslab;
+            const uint32_t first = ((uint32_t)wave + NW - next_item % NW) % NW;
+            next_item += items;
+            if (first >= items)
+                continue;
+            const Slot sl = slot[si];
             const Sched sc = sched[vi][si];
             const bool sps = (G.v_sched[vi] == KVS_SCHED_SPS);
             int32_t pk = 0;
             unsigned long long sumF = 0;
-            bool mine = false;
-            if (sl.n <= 64u) {
-                if (next_item % NW == (uint32_t)wave) {
-                    eval_sparse<PACKED>(sl, sc, sps, buf, n, J.s_scalar, F, lane, pk, sumF);
-                    mine = true;
-                }
-                next_item += 1;
+            if (n_runs <= 64u) {
+                eval_sparse<PACKED>(sl, sc, sps, buf, n, J.s_scalar, F, lane, pk, sumF);
             } else {
-                /* this wavefront's slabs: every NW-th, starting where the dealing has got to */
-                const uint32_t first = ((uint32_t)wave + NW - next_item % NW) % NW;
-                for (uint32_t j = first; j < sc.nslab; j += NW) {
+                for (uint32_t j = first; j < items; j += NW) {
                     if (sc.S == 0)
                         eval_thin<PACKED>(sl, sc, sps, j, buf, n, J.s_scalar, F, lane, pk, sumF);
                     else
                         eval_slab<PACKED, WIN>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk, sumF);
-                    mine = true;
                 }
-                next_item += sc.nslab;
             }
-            if (mine) {
-                pk = wave_max_nonneg(pk);
+            pk = wave_max_nonneg(pk);
+            if (lane == 0)
+                atomicMax(&res[vi][si].peak, pk);
+            if (!F.all_done) { /* else the table holds the closed form */
+                sumF = wave_sum_u63(sumF);
                 if (lane == 0)
-                    atomicMax(&res[vi][si].peak, pk);
-                if (!F.all_done) { /* else the table holds the closed form */
-                    sumF = wave_sum_u63(sumF);
-                    if (lane == 0)
-                        atomicAdd(&res[vi][si].sumF, sumF);
-                }
+                    atomicAdd(&res[vi][si].sumF, sumF);
             }
         }
     };
