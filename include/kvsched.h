@@ -189,6 +189,20 @@ int32_t kvs_paper_ladder(int64_t M, int64_t s, int32_t alpha_num, int32_t alpha_
 int32_t kvs_validate(const kvs_jobs_t *jobs, void *stream);
 
 /*
+ * kvs_validate for callers that cannot allocate device memory (tight serving
+ * loops, harnesses that forbid hipMalloc): the same scan and the same return
+ * values, but the scan's 12-byte result lives in a 256-byte array that is
+ * part of the library's device image (one copy per GPU, held until the
+ * process ends) instead of being allocated and freed by the call.  The result
+ * does not grow with the input, so no input is too large for it; the call
+ * allocates and frees nothing.  Every call on a GPU uses that GPU's one array
+ * (cleared by a small kernel at the start of each call): calls that overlap
+ * on the same GPU, from any threads or streams, race and may report each
+ * other's findings.  Waits for the stream like kvs_validate.
+ */
+int32_t kvs_validate_static(const kvs_jobs_t *jobs, void *stream);
+
+/*
  * The two bounds between which the analysis of GBA places its flow time
  * (Section "Analysis of GBA"), per instance, next to the schedules themselves:
  *

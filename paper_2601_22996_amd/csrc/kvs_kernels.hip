@@ -35,6 +35,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "kvsched.h"
 #include "kvs_math.h"
 #include "kvs_phase.h"
@@ -968,7 +970,47 @@ __global__ __launch_bounds__(256) void kvs_validate_kernel(JobsDev J, ValidateRe
         atomicOr(&res->infeasible, 1u);
 }
 
+/*
+ * Device memory for the entry point that allocates nothing: room for one ValidateResult.
+ * Every GPU the library runs on holds its own copy until the process ends.  In host code the
+ * name below is only a handle for hipGetSymbolAddress; kernels are handed the address that
+ * call returns.
+ */
+constexpr size_t kScratchBytes = 256;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+static_assert(sizeof(ValidateResult) <= kScratchBytes, "the scan's result fits the static scratch");
+
+__global__ void kvs_clear_result_kernel(ValidateResult *res)
+{
+    if (threadIdx.x == 0) {
+        res->bad_value = 0;
+        res->too_long = 0;
+        res->infeasible = 0;
+    }
+}
+
 /* ---- host side ---- */
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_addr[kMaxDevices]; /* per device: where its copy of `scratch` lives, once asked */
+
+/* Address of the current device's copy of the static scratch, looked up once per device. */
+int32_t static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return KVS_EHIP;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_addr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p)
+            return KVS_EHIP;
+        scratch_addr[dev] = p;
+    }
+    *ptr = scratch_addr[dev];
+    return KVS_OK;
+}
 
 int32_t check_jobs(const kvs_jobs_t *jobs)
 {
@@ -1324,6 +1366,48 @@ int32_t kvs_validate(const kvs_jobs_t *jobs, void *stream)
     if (hipStreamSynchronize(st) != hipSuccess)
         rc = KVS_EHIP;
     (void)hipFree(dres);
+    if (rc != KVS_OK)
+        return rc;
+    if (h.bad_value)
+        return KVS_EINVAL;
+    if (h.too_long)
+        return KVS_ERANGE;
+    if (h.infeasible)
+        return KVS_EJOB_INFEASIBLE;
+    return KVS_OK;
+}
+
+int32_t kvs_validate_static(const kvs_jobs_t *jobs, void *stream)
+{
+    int32_t rc = check_jobs(jobs);
+    if (rc != KVS_OK)
+        return rc;
+    if (jobs->n_instances == 0)
+        return KVS_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    void *p = nullptr;
+    rc = static_scratch(&p);
+    if (rc != KVS_OK)
+        return rc;
+    ValidateResult *dres = static_cast<ValidateResult *>(p);
+    ValidateResult h{0, 0, 0};
+    /* the last call's findings are still there: cleared by a kernel, not by a memset node */
+    hipLaunchKernelGGL(kvs_clear_result_kernel, dim3(1), dim3(64), 0, st, dres);
+    if (hipGetLastError() != hipSuccess)
+        return KVS_EHIP;
+    const size_t total = (size_t)jobs->n_instances * (size_t)jobs->n_jobs;
+    size_t blocks = (total + 255) / 256;
+    if (blocks > 256 * 32)
+        blocks = 256 * 32;
+    hipLaunchKernelGGL(kvs_validate_kernel, dim3((uint32_t)blocks), dim3(256), 0, st,
+                       to_dev(jobs, true), dres);
+    if (hipGetLastError() != hipSuccess)
+        rc = KVS_EHIP;
+    if (rc == KVS_OK &&
+        hipMemcpyAsync(&h, dres, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess)
+        rc = KVS_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess)
+        rc = KVS_EHIP;
     if (rc != KVS_OK)
         return rc;
     if (h.bad_value)

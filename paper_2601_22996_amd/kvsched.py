@@ -65,6 +65,8 @@ def lib():
         L.kvs_paper_ladder.argtypes = [C.c_int64, C.c_int64, i32, i32, C.POINTER(i32), C.POINTER(i32)]
         L.kvs_validate.restype = i32
         L.kvs_validate.argtypes = [C.POINTER(_Jobs), vp]
+        L.kvs_validate_static.restype = i32
+        L.kvs_validate_static.argtypes = [C.POINTER(_Jobs), vp]
         L.kvs_flow_bounds.restype = i32
         L.kvs_flow_bounds.argtypes = [C.POINTER(_Jobs), C.POINTER(i32), i32, vp, vp, vp]
         L.kvs_opt_perm.restype = i32
@@ -233,6 +235,12 @@ def validate(o: torch.Tensor, s, M: int, o_est: Optional[torch.Tensor] = None, s
     """kvs_validate: returns the status code (OK, EINVAL, ERANGE, EJOB_INFEASIBLE)."""
     jobs = _jobs(o, s, M, o_est)
     return int(lib().kvs_validate(C.byref(jobs), _stream(stream)))
+
+
+def validate_static(o: torch.Tensor, s, M: int, o_est: Optional[torch.Tensor] = None, stream=None) -> int:
+    """kvs_validate_static: kvs_validate without any device allocation."""
+    jobs = _jobs(o, s, M, o_est)
+    return int(lib().kvs_validate_static(C.byref(jobs), _stream(stream)))
 
 
 def version() -> int:
