@@ -34,12 +34,19 @@
  * Errors that depend on the job data cannot be returned by an asynchronous
  * call; they are reported in-band, per evaluation, in `feasible`:
  *   0 / 1                  the schedule exceeds / respects the budget M;
- *   KVS_FEASIBLE_EINVAL    some job of the instance has o < 1, s < 0,
- *                          o_est < 1 or s + o > M (per-job feasibility,
- *                          Section 2.1);
- *   KVS_FEASIBLE_ERANGE    the evaluation would leave the 32-bit range of the
- *                          device arithmetic (see "Limits").
- * In both error cases peak, flow and the remaining outputs of that evaluation
+ *   KVS_FEASIBLE_EINVAL    some job of the instance has o < 1, s < 0 or
+ *                          o_est < 1 (every point of the instance);
+ *   KVS_FEASIBLE_EJOB      some job has s + o > M: it does not fit the budget
+ *                          on its own, the per-job feasibility assumption of
+ *                          Section 2.1 fails (every point of the instance);
+ *   KVS_FEASIBLE_ERANGE    a length of the instance exceeds 2^30 (every
+ *                          point), or this evaluation would leave the 32-bit
+ *                          range of the device arithmetic in one of its own
+ *                          phases (see "Limits"; only the points whose phases
+ *                          do so).
+ * When several apply the order is EINVAL, ERANGE for a length, EJOB, ERANGE
+ * for a phase -- the order in which kvs_validate reports the first three.
+ * In every error case peak, flow and the remaining outputs of that evaluation
  * are -1.
  *
  * Limits: 1 <= n_jobs <= KVS_MAX_JOBS; lengths (o, s, o_est, tau) at most
@@ -63,11 +70,12 @@ extern "C" {
 
 #define KVS_OK 0
 #define KVS_EINVAL 1          /* bad argument: null pointer, size or parameter out of range */
-#define KVS_EJOB_INFEASIBLE 2 /* kvs_validate: some job has s + o > M               */
+#define KVS_EJOB_INFEASIBLE 2 /* kvs_validate: some job has s + o > M (in-band: KVS_FEASIBLE_EJOB) */
 #define KVS_ERANGE 3          /* kvs_validate: a length exceeds 2^30                */
 #define KVS_EHIP 4            /* a HIP runtime call failed                          */
 #define KVS_ELIMIT 5          /* n_jobs or n_pts above the compiled limits          */
 
+#define KVS_FEASIBLE_EJOB 0xFC
 #define KVS_FEASIBLE_EINVAL 0xFE
 #define KVS_FEASIBLE_ERANGE 0xFF
 

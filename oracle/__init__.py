@@ -7,8 +7,12 @@ smoke check and the CPU-baseline leg of the benchmark may import this package;
 the GPU library and its Python binding never do, and this package imports
 nothing of theirs.
 
-The C file is compiled with gcc on first use (and again when the source is
-newer than the library).
+Two C files: ``kvs_oracle.c`` is the oracle proper (literal stepping, the
+bounds, exhaustive search); ``kvs_events.c`` is a second, independently written
+evaluator of the same schedules from start / end events, fast enough to cover
+every instance of the largest workload, and trusted only where the tests show
+it equal to the stepper.  Both are compiled with gcc into one library on first
+use (and again when a source is newer than the library).
 """
 from __future__ import annotations
 
@@ -19,7 +23,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "kvs_oracle.c")
+_SRCS = [os.path.join(_HERE, "kvs_oracle.c"), os.path.join(_HERE, "kvs_events.c")]
 _LIB = os.path.join(_HERE, "libkvs_oracle.so")
 
 SPS, SIMS = 0, 1
@@ -35,11 +39,11 @@ class OracleError(RuntimeError):
 
 def build(force: bool = False) -> str:
     """Compile the C oracle into a shared library next to its source."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or any(os.path.getmtime(_LIB) < os.path.getmtime(p) for p in _SRCS)
     if force or stale:
         tmp = _LIB + f".tmp{os.getpid()}"
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", tmp, _SRC]
+            ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", tmp, *_SRCS]
         )
         os.replace(tmp, _LIB)
     return _LIB
@@ -90,6 +94,11 @@ def lib():
         _lib.kvo_area_lb.argtypes = [i64, p32, p32, i64, p64]
         _lib.kvo_upper_gba.restype = C.c_int
         _lib.kvo_upper_gba.argtypes = [i64, p32, p32, i64, i64, i64, p64]
+        _lib.kve_gba_simulate_batch.restype = C.c_int
+        _lib.kve_gba_simulate_batch.argtypes = _lib.kvo_gba_simulate_batch.argtypes
+        _lib.kve_ladder_simulate.restype = C.c_int
+        _lib.kve_ladder_simulate.argtypes = [i64, p32, p32, p32, i64, i64, p32, i64, C.c_int, i64,
+                                             C.c_int, p64, p32, p64, p64]
     return _lib
 
 
@@ -218,8 +227,12 @@ def ladder_simulate_batch(o, s, M, ladders, points, o_est=None, i0=0, i1=None):
     return dict(peak=peak, feasible=feas, flow=flow, job_steps=steps)
 
 
-def gba_simulate_batch(o, s, M, points, o_est=None, i0=0, i1=None):
+def gba_simulate_batch(o, s, M, points, o_est=None, i0=0, i1=None, threads=1, evaluator="stepper"):
     """Instances [i0, i1) of [I][n] arrays at every point (tau0, sched, k, mode).
+
+    `threads` > 1 runs disjoint instance ranges on that many threads (instances are independent; each
+    call into C is single-threaded and releases the interpreter lock).  `evaluator`: "stepper" is the
+    oracle proper (round by round), "events" the second evaluator of kvs_events.c.
 
     Returns dict of arrays shaped [n_pts][i1 - i0]."""
     o = _i32(o)
@@ -231,15 +244,46 @@ def gba_simulate_batch(o, s, M, points, o_est=None, i0=0, i1=None):
     pts = np.asarray(points, dtype=np.int32).reshape(-1, 4)
     tau0, sched, k, mode = (np.ascontiguousarray(pts[:, j]) for j in range(4))
     P, cnt = len(pts), i1 - i0
-    peak = np.zeros((P, cnt), np.int64)
-    flow = np.zeros((P, cnt), np.int64)
-    steps = np.zeros((P, cnt), np.int64)
-    feas = np.zeros((P, cnt), np.uint8)
-    _check(lib().kvo_gba_simulate_batch(i0, i1, n, _p32(o), _p32(s_arr), _p32(e), s_scalar, M,
-                                        P, _p32(tau0), _p32(sched), _p32(k), _p32(mode),
-                                        _p64(peak), feas.ctypes.data_as(C.POINTER(C.c_uint8)),
-                                        _p64(flow), _p64(steps)))
-    return dict(peak=peak, feasible=feas, flow=flow, job_steps=steps)
+    fn = {"stepper": lib().kvo_gba_simulate_batch, "events": lib().kve_gba_simulate_batch}[evaluator]
+    pu8 = C.POINTER(C.c_uint8)
+
+    def run(a, b):
+        part = dict(peak=np.zeros((P, b - a), np.int64), feasible=np.zeros((P, b - a), np.uint8),
+                    flow=np.zeros((P, b - a), np.int64), job_steps=np.zeros((P, b - a), np.int64))
+        rc = fn(a, b, n, _p32(o), _p32(s_arr), _p32(e), s_scalar, M, P, _p32(tau0), _p32(sched), _p32(k),
+                _p32(mode), _p64(part["peak"]), part["feasible"].ctypes.data_as(pu8), _p64(part["flow"]),
+                _p64(part["job_steps"]))
+        return rc, part
+
+    threads = max(1, min(int(threads), cnt))
+    if threads == 1:
+        rc, out = run(i0, i1)
+        _check(rc)
+        return out
+    from concurrent.futures import ThreadPoolExecutor
+    cuts = np.linspace(i0, i1, 4 * threads + 1).astype(np.int64)   # a few ranges per thread evens out the load
+    spans = [(int(a), int(b)) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+    with ThreadPoolExecutor(threads) as ex:
+        parts = list(ex.map(lambda ab: run(*ab), spans))
+    for rc, _ in parts:
+        _check(rc)
+    return {key: np.concatenate([part[key] for _, part in parts], axis=1)
+            for key in ("peak", "feasible", "flow", "job_steps")}
+
+
+def events_ladder_simulate(o, s, M, ladder, sched=SPS, k=0, mode=MODE_GBA, o_est=None):
+    """The second evaluator (kvs_events.c) on one instance and an explicit ladder of slices."""
+    o = _i32(o)
+    s_arr = None if np.isscalar(s) else _i32(s)
+    s_scalar = int(s) if np.isscalar(s) else 0
+    e = _i32(o_est)
+    lad = _i32(ladder)
+    peak, flow, steps = C.c_int64(), C.c_int64(), C.c_int64()
+    feas = C.c_int32()
+    _check(lib().kve_ladder_simulate(len(o), _p32(o), _p32(s_arr), _p32(e), s_scalar, M, _p32(lad),
+                                     len(lad), sched, k, mode, C.byref(peak), C.byref(feas),
+                                     C.byref(flow), C.byref(steps)))
+    return dict(peak=peak.value, feasible=feas.value, flow=flow.value, job_steps=steps.value)
 
 
 def schedule_eval_batch(o, s, M, points, i0=0, i1=None):

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SOURCES = [os.path.join(HERE, "csrc", "kvs_kernels.hip"), os.path.join(HERE, "csrc", "kvs_bounds.hip")]
 HEADERS = [os.path.join(HERE, "csrc", h) for h in ("kvs_math.h", "kvs_wave.h", "kvs_phase.h")] + \
-          [os.path.join(ROOT, "include", "kvsched.h")]
+          [os.path.join(ROOT, "include", h) for h in ("kvsched.h", "kvsched_test.h")]
 LIB = os.path.join(HERE, "libkvsched.so")
 
 HIPCC_FLAGS = [

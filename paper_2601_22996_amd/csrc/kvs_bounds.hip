@@ -15,6 +15,7 @@
 
 #include "kvs_math.h"
 #include "kvsched.h"
+#include "kvsched_test.h"
 
 namespace {
 

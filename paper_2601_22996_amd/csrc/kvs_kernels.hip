@@ -38,6 +38,7 @@
 #include <mutex>
 
 #include "kvsched.h"
+#include "kvsched_test.h"
 #include "kvs_math.h"
 #include "kvs_phase.h"
 #include "kvs_wave.h"
@@ -50,8 +51,10 @@ constexpr int kMaxM = 8;               /* distinct shifts m per launch          
 constexpr int kMaxV = 4;               /* distinct (subroutine, parallelism) variants per launch        */
 constexpr uint32_t kLenMax = 1u << 30; /* largest length the 32-bit arithmetic is sized for             */
 
-constexpr uint32_t FLAG_EINVAL = 1u;
-constexpr uint32_t FLAG_ERANGE = 2u;
+/* what is wrong with an instance's job data; any of these and none of its points is evaluated */
+constexpr uint32_t FLAG_EINVAL = 1u; /* o < 1, s < 0, o_est < 1, or no slice of an explicit ladder covers a job */
+constexpr uint32_t FLAG_ERANGE = 2u; /* a length above 2^30                                                       */
+constexpr uint32_t FLAG_EJOB = 4u;   /* s + o > M: the job does not fit the budget on its own (Section 2.1)        */
 constexpr uint8_t FEASIBLE_PENDING = 0xFD; /* internal: left for the two-word-entry kernel */
 
 constexpr int MODE_GBA = 0, MODE_GSA = 1, MODE_SINGLE = 2;
@@ -95,7 +98,7 @@ struct JobView {
     uint32_t ga; /* level at which it first takes part           */
     uint32_t gb; /* level at which it takes part for the last time */
     uint32_t go; /* level of o: it completes in phases that reach it */
-    bool valid;
+    uint32_t bad; /* FLAG_* bits, 0 for a job that can be scheduled */
 };
 
 /* A job as it sits in memory. */
@@ -122,11 +125,8 @@ __device__ __forceinline__ uint32_t level_of(uint32_t x, const GroupArg &G, cons
 {
     if (!EXPLICIT)
         return kvs_class_index(x, G.base, G.lg_base);
-    uint32_t p = 0; /* number of slices below x */
-#pragma unroll
-    for (uint32_t b = kLevelsMax / 2; b > 0; b >>= 1)
-        if (p + b - 1u < G.n_lv && lad[p + b - 1u] < x)
-            p += b;
+    static_assert(kLevelsMax == 64, "kvs_ladder_level searches 64 slices");
+    uint32_t p = kvs_ladder_level(x, lad, G.n_lv);
     if (p >= G.n_lv) {
         ok = false;
         p = G.n_lv - 1u;
@@ -141,29 +141,40 @@ __device__ __forceinline__ JobView view_job(const RawJob &r, const JobsDev &J, c
     JobView v;
     const int32_t o = r.o;
     const int32_t s = r.s;
-    v.valid = (o >= 1) && (s >= 0) && ((uint32_t)o <= kLenMax) && ((uint32_t)s <= kLenMax) &&
-              ((uint64_t)(uint32_t)s + (uint64_t)(uint32_t)o <= J.M);
+    bool covered = true; /* some slice of an explicit ladder reaches the length */
+    v.bad = 0;
+    if (o < 1 || s < 0)
+        v.bad = FLAG_EINVAL;
+    else if ((uint32_t)o > kLenMax || (uint32_t)s > kLenMax)
+        v.bad = FLAG_ERANGE;
+    else if ((uint64_t)(uint32_t)s + (uint64_t)(uint32_t)o > J.M)
+        v.bad = FLAG_EJOB;
     v.o = (o < 1) ? 1u : ((uint32_t)o > kLenMax ? kLenMax : (uint32_t)o);
     v.s = (s < 0) ? 0u : ((uint32_t)s > kLenMax ? kLenMax : (uint32_t)s);
-    v.go = level_of<EXPLICIT>(v.o, G, lad, v.valid);
+    v.go = level_of<EXPLICIT>(v.o, G, lad, covered);
     if (mode != MODE_GBA) { /* GSA, or one invocation of the subroutine: everybody from the start */
         v.ga = 0;
         v.gb = v.go;
     } else if (with_estimates) {
         const int32_t e = r.e;
-        v.valid = v.valid && (e >= 1);
+        if (e < 1)
+            v.bad |= FLAG_EINVAL;
+        else if ((uint32_t)e > kLenMax)
+            v.bad |= FLAG_ERANGE;
         uint64_t cap = (J.M > v.s) ? (J.M - v.s) : 1u; /* M - s, at least 1 */
         if (cap > kLenMax)
             cap = kLenMax;
         uint32_t eu = (e < 1) ? 1u : (uint32_t)e;
         if (eu > (uint32_t)cap)
             eu = (uint32_t)cap;
-        v.ga = level_of<EXPLICIT>(eu, G, lad, v.valid);
+        v.ga = level_of<EXPLICIT>(eu, G, lad, covered);
         v.gb = v.ga > v.go ? v.ga : v.go;
     } else {
         v.ga = v.go;
         v.gb = v.go;
     }
+    if (!covered)
+        v.bad |= FLAG_EINVAL;
     return v;
 }
 
@@ -259,11 +270,11 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         uint32_t *myE = histE + (lane & (kRep - 1)) * kRowE;
         unsigned long long sumO = 0;
         uint32_t mxO = 0, mxS = 0, mxG = 0;
-        bool inval = false;
+        uint32_t badbits = 0;
         const bool want_e = with_estimates;
         auto account = [&](const RawJob &raw, uint32_t i) {
             const JobView v = view_job<EXPLICIT>(raw, J, G, lad, mode, with_estimates);
-            inval |= !v.valid;
+            badbits |= v.bad;
             if (mode != MODE_SINGLE || v.go == 0)
                 sumO += v.o; /* every job completes once; a lone invocation completes o <= tau */
             mxO = v.o > mxO ? v.o : mxO;
@@ -366,8 +377,13 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
             atomicMax(&maxS_sh, mxS);
             atomicMax(&maxE_sh, mxG);
         }
-        if (__any(inval) && lane == 0)
-            atomicOr(&flags, FLAG_EINVAL);
+        if (__any(badbits != 0)) {
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1)
+                badbits |= __shfl_xor(badbits, off);
+            if (lane == 0)
+                atomicOr(&flags, badbits);
+        }
     }
     __syncthreads();
 
@@ -435,6 +451,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         sl.tau = 0;
         sl.off = 0;
         sl.alias = (uint32_t)tid;
+        sl.bad = 0;
         sl.divtau = kvs_make_divisor(1);
         uint32_t lv = 0;
         bool used = false;
@@ -478,8 +495,8 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         }
         if (used && sl.n > 0) {
             const uint64_t tau = lad[lv];
-            if (tau * sl.n >= (1ull << 31)) {
-                atomicOr(&flags, FLAG_ERANGE);
+            if (tau * sl.n >= (1ull << 31)) { /* the points that use this phase are out of range */
+                sl.bad = 1;
                 sl.n = 0;
             } else {
                 sl.tau = (uint32_t)tau;
@@ -502,6 +519,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         sc.H = 0;
         sc.S = 64;
         sc.nslab = 0;
+        sc.bad = 0;
         sc.div = kvs_make_divisor(1);
         if (sl.n > 0) {
             const uint64_t tau = sl.tau, smax = sl.smax, np = sl.n;
@@ -519,7 +537,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
                 k = kcap;
             const uint64_t act = (k < np) ? k : np;
             if (act * (smax + tau + WIN + 1) >= (1ull << 31)) /* window sums stay in 32 bits */
-                atomicOr(&flags, FLAG_ERANGE);
+                sc.bad = 1;
             sc.k = (uint32_t)k;
             sc.div = kvs_make_divisor(sc.k);
             sc.H = start_offset(sl.n - 1, sl.tau, sc, sps) + sl.tau;
@@ -541,6 +559,10 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
                 sc.S = 0;
                 sc.nslab = (sl.n + 63u) / 64u;
             }
+            if (sl.n <= 64u)
+                sc.nslab = 1; /* one wavefront, one run per lane */
+            if (sc.bad)
+                sc.nslab = 0; /* out of range: not evaluated, and its points say so */
         }
         sched[vi][si] = sc;
         res[vi][si].peak = 0;
@@ -570,7 +592,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
             /* work items of this (slot, variant): one for a phase of at most 64 runs, else its
              * slabs (or groups of runs).  This wavefront takes every NW-th, starting where the
              * dealing has got to, and reads the tables only if something falls to it. */
-            const uint32_t items = n_runs <= 64u ? 1u : sched[vi][si].nslab;
+            const uint32_t items = sched[vi][si].nslab;
             const uint32_t first = ((uint32_t)wave + NW - next_item % NW) % NW;
             next_item += items;
             if (first >= items)
@@ -882,10 +904,11 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
         const int g = (int)G.m[mi] + j;
         const bool in_ladder = have && !bad && (j == 0 || (mode != MODE_SINGLE && g < kLevels));
         unsigned long long H = 0, sumF = 0;
-        uint32_t n_p = 0, done_p = 0, tau_p = 0;
+        uint32_t n_p = 0, done_p = 0, tau_p = 0, err = 0;
         int32_t pk = 0;
         if (in_ladder) {
             const Slot sl = slot[j == 0 ? kLevels + mi : g];
+            err = sl.bad | sched[vi][sl.alias].bad; /* a phase of this point left the 32-bit range */
             if (sl.n > 0) {
                 const Result r = res[vi][sl.alias];
                 n_p = sl.n;
@@ -912,6 +935,7 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
             flow += __shfl_xor(flow, d, kLevels);
             steps += __shfl_xor(steps, d, kLevels);
             done += __shfl_xor(done, d, kLevels);
+            err |= __shfl_xor(err, d, kLevels);
             const int32_t other = __shfl_xor(pk, d, kLevels);
             pk = other > pk ? other : pk;
         }
@@ -923,7 +947,11 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
                 feas = KVS_FEASIBLE_EINVAL;
             else if (flags & FLAG_ERANGE)
                 feas = KVS_FEASIBLE_ERANGE;
-            if (bad)
+            else if (flags & FLAG_EJOB)
+                feas = KVS_FEASIBLE_EJOB;
+            else if (err)
+                feas = KVS_FEASIBLE_ERANGE;
+            if (bad || err)
                 peak = fl = st = dn = -1;
             const size_t oi = (size_t)G.pt_q[q] * (size_t)J.n_inst + inst;
             out.peak[oi] = peak;
@@ -1434,10 +1462,15 @@ const char *kvs_strerror(int32_t status)
 
 int32_t kvs_version(void) { return 400; }
 
-/* Host evaluation of the kernels' integer helpers, for the host-side tests. */
+/* Host evaluation of the kernels' integer helpers, for the host-side tests (kvsched_test.h). */
 uint32_t kvs_host_class_index(uint32_t x, uint32_t tau0)
 {
     return kvs_class_index(x, tau0, kvs_ilog2_floor(tau0));
+}
+
+uint32_t kvs_host_ladder_level(uint32_t x, const uint32_t *lad, uint32_t n_lv)
+{
+    return kvs_ladder_level(x, lad, n_lv);
 }
 
 uint32_t kvs_host_div(uint32_t x, uint32_t d) { return kvs_div(x, kvs_make_divisor(d)); }

@@ -60,6 +60,27 @@ KVS_HD uint32_t kvs_class_index(uint32_t x, uint32_t tau0, uint32_t lg_tau0)
 }
 
 /*
+ * Level of a length x on an explicit ladder lad[0] <= lad[1] <= ... <= lad[n_lv - 1]
+ * (1 <= n_lv <= 64): the number of slices below x, which is the index of the first slice
+ * that covers x, or n_lv when none does.  Six halving steps find the largest p <= 63 whose
+ * p slices in front are all below x; the last slice of a 64-slice ladder is then looked at
+ * on its own.
+ */
+KVS_HD uint32_t kvs_ladder_level(uint32_t x, const uint32_t *lad, uint32_t n_lv)
+{
+    uint32_t p = 0;
+#if defined(__HIP_DEVICE_COMPILE__)
+#pragma unroll
+#endif
+    for (uint32_t b = 32u; b > 0u; b >>= 1)
+        if (p + b - 1u < n_lv && lad[p + b - 1u] < x)
+            p += b;
+    if (p < n_lv && lad[p] < x)
+        p++;
+    return p;
+}
+
+/*
  * Division of 31-bit dividends by a constant d >= 1 through one multiply-high
  * and a shift: with l = ceil(log2 d) and mul = floor(2^(31+l) / d) + 1,
  * floor(x * mul / 2^(31+l)) = floor(x / d) for every 0 <= x < 2^31

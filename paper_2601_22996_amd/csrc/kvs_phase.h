@@ -28,6 +28,7 @@ struct Slot {
     uint32_t tau;   /* slice length                                      */
     uint32_t off;   /* where its entries start in the phase buffer       */
     uint32_t alias; /* slot whose results it shares, or its own index    */
+    uint32_t bad;   /* n * tau leaves 31 bits: the phase is not evaluated */
     kvs_divisor_t divtau; /* division by tau                             */
 };
 
@@ -36,7 +37,9 @@ struct Sched {
     uint32_t k; /* parallelism (SPS) or batch size (SimS), >= 1          */
     uint32_t H; /* rounds the phase lasts                                */
     uint32_t S; /* slab length used to evaluate it; 0: by runs, not by rounds (eval_thin) */
-    uint32_t nslab; /* work items: slabs of S rounds, or groups of 64 runs */
+    uint32_t nslab; /* work items: slabs of S rounds, groups of 64 runs, 1 for a phase of at most
+                       64 runs, 0 when there is nothing to evaluate        */
+    uint32_t bad;   /* the window sums could leave 32 bits: not evaluated  */
     kvs_divisor_t div;
 };
 

@@ -18,7 +18,7 @@ from . import build as _build
 
 SPS, SIMS = 0, 1
 MODE_GBA, MODE_GSA = 0, 1
-FEASIBLE_EINVAL, FEASIBLE_ERANGE = 0xFE, 0xFF
+FEASIBLE_EJOB, FEASIBLE_EINVAL, FEASIBLE_ERANGE = 0xFC, 0xFE, 0xFF
 OK, EINVAL, EJOB_INFEASIBLE, ERANGE, EHIP, ELIMIT = 0, 1, 2, 3, 4, 5
 MAX_JOBS, MAX_POINTS, MAX_LEVELS = 16384, 64, 64
 
@@ -47,10 +47,11 @@ def library_path() -> str:
 
 
 def lib():
-    """The loaded shared library; built first only if no built library exists."""
+    """The loaded shared library; built first when there is none or a source is newer than it
+    (a library older than its sources would run something else than the code in the tree)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.LIB):
+        if _build.is_stale():
             _build.build()
         L = C.CDLL(_build.LIB)
         vp, i32 = C.c_void_p, C.c_int32
@@ -74,18 +75,6 @@ def lib():
         L.kvs_strerror.restype = C.c_char_p
         L.kvs_strerror.argtypes = [i32]
         L.kvs_version.restype = i32
-        L.kvs_host_class_index.restype = C.c_uint32
-        L.kvs_host_class_index.argtypes = [C.c_uint32, C.c_uint32]
-        L.kvs_host_div.restype = C.c_uint32
-        L.kvs_host_div.argtypes = [C.c_uint32, C.c_uint32]
-        L.kvs_host_kstar.restype = C.c_uint64
-        L.kvs_host_kstar.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
-        L.kvs_host_floor_sum.restype = C.c_uint64
-        L.kvs_host_floor_sum.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
-        L.kvs_host_best_of_unit.restype = C.c_int64
-        L.kvs_host_best_of_unit.argtypes = [C.c_uint32, i32, C.POINTER(i32), C.c_int64, C.c_int64]
-        L.kvs_host_perm_units.restype = C.c_uint32
-        L.kvs_host_perm_units.argtypes = [i32]
         _lib = L
     return _lib
 
@@ -104,6 +93,14 @@ def _dev_i32(t: Optional[torch.Tensor], shape, name: str) -> Optional[int]:
         return None
     if not (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous() and tuple(t.shape) == tuple(shape)):
         raise ValueError(f"{name}: need a contiguous int32 device tensor of shape {tuple(shape)}")
+    return t.data_ptr()
+
+
+def _dev_out(out: dict, name: str, shape, dtype, device) -> int:
+    t = out.get(name)
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.device == device and t.dtype == dtype
+            and t.is_contiguous() and tuple(t.shape) == tuple(shape)):
+        raise ValueError(f"out[{name!r}]: need a contiguous {dtype} tensor of shape {tuple(shape)} on {device}")
     return t.data_ptr()
 
 
@@ -135,9 +132,10 @@ def gba_simulate(o: torch.Tensor, s, M: int, points, o_est: Optional[torch.Tenso
                    job_steps=torch.empty((P, I), dtype=torch.int64, device=o.device))
     arr = (_Point * max(P, 1))(*[_Point(*map(int, r)) for r in pts])
     jobs = _jobs(o, s, M, o_est)
-    _check(lib().kvs_gba_simulate(C.byref(jobs), arr, P, out["peak"].data_ptr(),
-                                  out["feasible"].data_ptr(), out["flow"].data_ptr(),
-                                  out["job_steps"].data_ptr(), _stream(stream)))
+    _check(lib().kvs_gba_simulate(C.byref(jobs), arr, P, _dev_out(out, "peak", (P, I), torch.int64, o.device),
+                                  _dev_out(out, "feasible", (P, I), torch.uint8, o.device),
+                                  _dev_out(out, "flow", (P, I), torch.int64, o.device),
+                                  _dev_out(out, "job_steps", (P, I), torch.int64, o.device), _stream(stream)))
     return out
 
 
@@ -216,8 +214,9 @@ def flow_bounds(o: torch.Tensor, s, M: int, tau0: Sequence[int], area: bool = Tr
     arr = (C.c_int32 * max(P, 1))(*map(int, tau0))
     jobs = _jobs(o, s, M, None)
     a = out.get("area_lb_num")
-    _check(lib().kvs_flow_bounds(C.byref(jobs), arr, P, out["upper_gba"].data_ptr(),
-                                 a.data_ptr() if a is not None else None, _stream(stream)))
+    _check(lib().kvs_flow_bounds(C.byref(jobs), arr, P, _dev_out(out, "upper_gba", (P, I), torch.int64, o.device),
+                                 _dev_out(out, "area_lb_num", (I,), torch.int64, o.device) if a is not None else None,
+                                 _stream(stream)))
     return out
 
 
@@ -227,7 +226,8 @@ def opt_perm(o: torch.Tensor, s: int, M: int, out: Optional[torch.Tensor] = None
     if out is None:
         out = torch.empty((o.shape[0],), dtype=torch.int64, device=o.device)
     jobs = _jobs(o, int(s), M, None)
-    _check(lib().kvs_opt_perm(C.byref(jobs), out.data_ptr(), _stream(stream)))
+    _check(lib().kvs_opt_perm(C.byref(jobs), _dev_out({"best_flow": out}, "best_flow", (o.shape[0],), torch.int64,
+                                                      o.device), _stream(stream)))
     return out
 
 

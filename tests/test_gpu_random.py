@@ -1,0 +1,178 @@
+"""Seeded randomized comparison of the HIP library with the CPU oracle, through
+the C ABI: many small and medium instances over shapes, value ranges, modes and
+entry points that the hand-written cases do not enumerate.  Every case is
+drawn from its own seed, is bit-exact or fails, and is printed when it fails so
+that it can be run again alone."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle as O
+
+KEYS = ("peak", "feasible", "flow", "job_steps")
+# sizes around the boundaries of the kernels' tiles: wavefront (64), the workgroup sizes
+# (256, 512, 768), the instantiation switch (4096), the hold limits (768 * 14) and the cap
+SIZES = [1, 2, 3, 7, 31, 63, 64, 65, 100, 255, 256, 257, 511, 513, 767, 768, 769, 1023, 1025, 1536, 2047,
+         3000, 4095, 4096, 4097, 4500, 5000, 6143, 6145, 8191, 8193, 9999, 10752, 10753, 12000, 14336, 16384]
+
+
+@pytest.fixture(scope="module")
+def K():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2601_22996_amd import kvsched
+    kvsched.lib()
+    return kvsched
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def draw_jobs(rng, big_bias):
+    """Lengths, prompts, budget and (sometimes) estimates of a few instances."""
+    n = int(rng.choice(SIZES[18:] if big_bias else SIZES))
+    I = int(rng.integers(1, 4)) if n > 2000 else int(rng.integers(1, 9))
+    omax = int(rng.choice([1, 2, 5, 40, 300, 3000, 40000]))
+    if n > 3000:
+        omax = min(omax, 3000)          # keeps the stepper's work per case bounded
+    law = int(rng.integers(0, 4))
+    if law == 0:
+        o = np.minimum(rng.geometric(1.0 / max(1.5, omax / 5), (I, n)), omax)
+    elif law == 1:
+        o = rng.integers(1, omax + 1, (I, n))
+    elif law == 2:
+        o = np.clip((2 * rng.random((I, n)) ** (-1 / 1.3)).astype(np.int64), 1, omax)
+    else:
+        o = np.full((I, n), omax)
+        o[rng.random((I, n)) < 0.3] = max(1, omax // 3)
+    o = o.astype(np.int32)
+    smax = int(rng.choice([0, 1, 50, 5000, 70000]))   # 70000 needs the two-word entries; 16384 jobs in flight
+    #                                                    with such prompts still sum below 2^31
+    hetero = bool(rng.integers(0, 2))
+    s = rng.integers(0, smax + 1, (I, n)).astype(np.int32) if hetero else int(rng.integers(0, smax + 1))
+    M = int(omax + smax + rng.choice([0, 1, 100, 5000, 200000]))
+    e = None
+    if rng.integers(0, 3) == 0:
+        e = np.clip(np.rint(o * np.exp(rng.normal(0, 0.7, o.shape))), 1, None).astype(np.int32)
+    return dict(n=n, I=I, omax=omax, law=law, smax=smax, hetero=hetero, o=o, s=s, M=M, e=e)
+
+
+def compare(got, want, keys, label):
+    for key in keys:
+        g, w = got[key].cpu().numpy(), want[key]
+        if not np.array_equal(g, w):
+            bad = np.argwhere(g != w)
+            raise AssertionError(f"{label}: {key} differs at {len(bad)} places, first {tuple(bad[0])}: "
+                                 f"gpu {g[tuple(bad[0])]} oracle {w[tuple(bad[0])]}")
+
+
+def sweep_case(K, seed):
+    rng = np.random.default_rng(seed)
+    j = draw_jobs(rng, big_bias=(seed % 3 == 0))
+    o, s, M, e = j["o"], j["s"], j["M"], j["e"]
+    kind = int(rng.integers(0, 3))
+    label = (f"seed {seed}: n={j['n']} I={j['I']} law={j['law']} omax={j['omax']} smax={j['smax']} "
+             f"hetero={j['hetero']} M={M} estimates={e is not None} kind={kind}")
+    sa = s if np.isscalar(s) else dev(s)
+    if kind == 0:       # kvs_gba_simulate: doubling ladders, both subroutines, forced k, both modes
+        P = int(rng.integers(1, 13))
+        pts = [(int(rng.choice([1, 2, 3, 4, 6, 8, 16, 32, 100, 128, 1000])), int(rng.integers(0, 2)),
+                int(rng.choice([0, 0, 0, 1, 3, 64, 100000])), int(rng.integers(0, 2))) for _ in range(P)]
+        got = K.gba_simulate(dev(o), sa, M, pts, o_est=dev(e))
+        torch.cuda.synchronize()
+        compare(got, O.gba_simulate_batch(o, s, M, pts, e), KEYS, label + f" pts={pts}")
+    elif kind == 1:     # kvs_schedule_eval: one invocation of the subroutine
+        P = int(rng.integers(1, 9))
+        tau = [int(x) for x in rng.choice([1, 2, 7, 64, max(1, j["omax"] // 2), j["omax"], 2 * j["omax"]], P)]
+        k = [int(x) for x in rng.choice([0, 0, 1, 5, 200, 100000], P)]
+        sc = [int(x) for x in rng.integers(0, 2, P)]
+        got = K.schedule_eval(dev(o), sa, M, tau, k, sc)
+        torch.cuda.synchronize()
+        compare(got, O.schedule_eval_batch(o, s, M, list(zip(tau, k, sc))), KEYS + ("n_completed",),
+                label + f" tau={tau} k={k} sched={sc}")
+    else:               # kvs_ladder_simulate: explicit ladders, irregular growth, up to 64 slices
+        top = int(max(j["omax"], e.max() if e is not None else 1))
+        lads = []
+        for _ in range(int(rng.integers(1, 4))):
+            a = float(rng.choice([1.12, 1.3, 1.5, 2.0, 3.0]))
+            lad = [int(rng.integers(1, 4))]
+            while lad[-1] < top and len(lad) < 64:
+                lad.append(max(lad[-1] + int(rng.integers(0, 2)), int(lad[-1] * a)))
+            lad[-1] = max(lad[-1], top)                 # the last slice covers every job
+            lads.append(np.array(lad, np.int32))
+        use, pts = [], []
+        for lad in lads:
+            for _ in range(int(rng.integers(1, 4))):
+                use.append(lad)
+                pts.append((int(rng.integers(0, 2)), int(rng.choice([0, 0, 2, 77])), int(rng.integers(0, 2))))
+        got = K.ladder_simulate(dev(o), sa, M, use, pts, o_est=dev(e))
+        torch.cuda.synchronize()
+        compare(got, O.ladder_simulate_batch(o, s, M, use, pts, e), KEYS,
+                label + f" ladders={[l.tolist() for l in lads]} pts={pts}")
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_sweeps(K, block):
+    for seed in range(7000 + 100 * block, 7000 + 100 * (block + 1)):
+        sweep_case(K, seed)
+
+
+def bounds_case(K, seed):
+    rng = np.random.default_rng(seed)
+    if seed % 3 == 2:   # kvs_opt_perm on tiny instances
+        n, I = int(rng.integers(1, 9)), int(rng.integers(1, 30))
+        omax, s = int(rng.choice([1, 3, 12, 40])), int(rng.integers(0, 30))
+        o = rng.integers(1, omax + 1, (I, n)).astype(np.int32)
+        M = s + omax + int(rng.choice([0, 1, 5, 30, 300]))
+        got = K.opt_perm(dev(o), s, M)
+        torch.cuda.synchronize()
+        want = np.array([O.opt_perm(o[i], s, M) for i in range(I)])
+        assert np.array_equal(got.cpu().numpy(), want), f"seed {seed}: opt_perm n={n} I={I} omax={omax} s={s} M={M}"
+        return
+    n = int(rng.choice([1, 2, 5, 15, 16, 17, 100, 255, 1000, 1023, 1024, 1025, 2000, 4095, 4096, 4097, 7000, 10000, 16384]))
+    I = int(rng.integers(1, 6)) if n > 1100 else int(rng.integers(1, 20))
+    omax = int(rng.choice([1, 4, 60, 900, 20000, 300000]))
+    smax = int(rng.choice([0, 3, 200, 9000, 400000]))
+    law = int(rng.integers(0, 3))
+    if law == 0:
+        o = np.minimum(rng.geometric(1.0 / max(1.5, omax / 6), (I, n)), omax)
+    elif law == 1:
+        o = rng.integers(1, omax + 1, (I, n))
+    else:
+        o = np.clip((3 * rng.random((I, n)) ** (-1 / 1.2)).astype(np.int64), 1, omax)
+    o = o.astype(np.int32)
+    hetero = bool(rng.integers(0, 2))
+    s = rng.integers(0, smax + 1, (I, n)).astype(np.int32) if hetero else int(rng.integers(0, smax + 1))
+    M = int(omax + smax + rng.choice([0, 10, 5000, 10 ** 6]))
+    tau0 = [int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 64, 100, 1000, 4096, 65536])) for _ in range(int(rng.integers(0, 9)))]
+    label = f"seed {seed}: bounds n={n} I={I} omax={omax} smax={smax} hetero={hetero} M={M} tau0={tau0}"
+    r = K.flow_bounds(dev(o), s if np.isscalar(s) else dev(s), M, tau0)
+    torch.cuda.synchronize()
+    up, ar = r["upper_gba"].cpu().numpy(), r["area_lb_num"].cpu().numpy()
+    for i in range(I):
+        si = s if np.isscalar(s) else s[i]
+        try:
+            wa = O.area_lb(o[i], si)
+        except O.OracleError:       # the sum itself leaves 63 bits
+            wa = None
+        if ar[i] == -1 or wa is None:   # allowed only when n (n + 1) / 2 times the largest area reaches 2^63
+            assert ar[i] == -1, label + f": area bound of instance {i} must be flagged"
+            amx = int((np.int64(1) * o[i] * si + o[i].astype(np.int64) * (o[i] + 1) // 2).max())
+            assert n * (n + 1) // 2 * amx >= 2 ** 63, label + f": area bound of instance {i} flagged without cause"
+        else:
+            assert ar[i] == wa, label + f": area bound of instance {i}: gpu {ar[i]} oracle {wa}"
+        for q, t in enumerate(tau0):
+            wu = O.upper_gba(o[i], si, M, t)
+            if up[q, i] == -1:  # allowed only when some class has n_p tau_p >= 2^31
+                assert n * max(t, 2 * int(o[i].max())) >= 2 ** 31, label + f": UpperGBA {q},{i} flagged without cause"
+            else:
+                assert up[q, i] == wu, label + f": UpperGBA of point {q} instance {i}: gpu {up[q, i]} oracle {wu}"
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_random_bounds(K, block):
+    for seed in range(9000 + 100 * block, 9000 + 100 * (block + 1)):
+        bounds_case(K, seed)

@@ -24,6 +24,8 @@ def L():
     lib.kvs_host_div.argtypes = [C.c_uint32, C.c_uint32]
     lib.kvs_host_kstar.restype = C.c_uint64
     lib.kvs_host_kstar.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
+    lib.kvs_host_ladder_level.restype = C.c_uint32
+    lib.kvs_host_ladder_level.argtypes = [C.c_uint32, C.POINTER(C.c_uint32), C.c_uint32]
     lib.kvs_strerror.restype = C.c_char_p
     return lib
 
@@ -39,10 +41,16 @@ def test_built_library_is_not_older_than_its_sources():
 def test_exports_every_declared_symbol(L):
     header = open(os.path.join(ROOT, "include", "kvsched.h")).read()
     names = set(re.findall(r"\b(kvs_[a-z_]+)\s*\(", header))
-    assert {"kvs_gba_simulate", "kvs_schedule_eval", "kvs_validate", "kvs_strerror",
+    assert {"kvs_gba_simulate", "kvs_schedule_eval", "kvs_validate", "kvs_validate_static", "kvs_strerror",
             "kvs_version"} <= names
-    for name in names:
+    assert not any(n.startswith("kvs_host_") for n in names), "test hooks belong in kvsched_test.h"
+    hooks = set(re.findall(r"\b(kvs_[a-z_]+)\s*\(", open(os.path.join(ROOT, "include", "kvsched_test.h")).read()))
+    assert hooks and all(n.startswith("kvs_host_") for n in hooks)
+    for name in names | hooks:
         assert hasattr(L, name), name
+    # the product binding marshals the product interface only
+    binding = open(os.path.join(ROOT, "paper_2601_22996_amd", "kvsched.py")).read()
+    assert "kvs_host_" not in binding
     assert L.kvs_version() >= 100
     assert L.kvs_strerror(0) == b"ok"
 
@@ -87,6 +95,22 @@ def test_class_index_matches_definition(L):
     for t in list(range(1, 40)) + [100, 1000, 2 ** 20, 2 ** 30 - 1, 2 ** 30]:
         for x in list(range(1, 200)) + [2 ** 30, 2 ** 30 - 1, 2 ** 29 + 1, 2 ** 20 + 3]:
             assert L.kvs_host_class_index(x, t) == cls(x, t), (x, t)
+
+
+def test_ladder_level_counts_the_slices_below_a_length(L):
+    # explicit ladders of every length up to the limit, lengths at, between, below and above the
+    # slices; a length above the last slice has no level (answer n_lv), also on a full 64-slice ladder
+    rng = random.Random(11)
+    for n_lv in list(range(1, 9)) + [31, 32, 33, 62, 63, 64]:
+        for _ in range(20):
+            lad = sorted(rng.randrange(1, 5000) for _ in range(n_lv))
+            arr = (C.c_uint32 * n_lv)(*lad)
+            xs = {1, lad[0], lad[-1], lad[-1] + 1, 2 ** 30} | {v + d for v in lad for d in (-1, 0, 1) if v + d >= 1}
+            for x in xs:
+                want = sum(1 for v in lad if v < x)
+                assert L.kvs_host_ladder_level(x, arr, n_lv) == want, (n_lv, x, lad)
+    full = (C.c_uint32 * 64)(*range(1, 65))
+    assert L.kvs_host_ladder_level(64, full, 64) == 63 and L.kvs_host_ladder_level(65, full, 64) == 64
 
 
 def test_constant_division_is_exact_below_2_31(L):

@@ -579,3 +579,108 @@ def test_area_lower_bound():
         M = int(rng.integers(s + 8, 30))
         assert O.area_lb(o, s) <= O.opt_exact(o, s, M) * M
         assert O.area_lb(o, s) == _area_lb_times_M(o.tolist(), s)
+
+
+# --------------------------------------------------------------------------
+# The estimate rule worked by hand (the paper prints no value for it): a job
+# is classed by what the scheduler believes, killed at the end of its slice
+# while its true length exceeds the slice (Procedure 1) and kept for the next
+# phase (Algorithm 1's "keep the unfinished jobs"); an over-estimated job waits
+# for the phase whose slice covers the estimate.
+# --------------------------------------------------------------------------
+HAND_ESTIMATE_CASES = [
+    # Under-estimated job killed three times.  s = 0, M = 100, slices 1, 2, 4, 8.  k*(1, 0, 100) = 100
+    # (Peak(k, 1, 0) = k), so both jobs of phase 0 start in round 0.  Job 1 (o = 1) completes at 1.
+    # Job 0 (o = 5, believed 1) runs 1 round and is killed; alone in phase 1 (begins 1, slice 2) it
+    # is killed at 3; alone in phase 2 (begins 3, slice 4) it is killed at 7; in phase 3 (begins 7,
+    # slice 8) it completes at 12.  Flow 1 + 12; steps 1 + (1 + 2 + 4 + 5); the peak is its last
+    # round, progress 4: 0 + 4 + 1.
+    dict(o=[5, 1], e=[1, 1], s=0, M=100, tau0=1, sched=O.SPS,
+         want=dict(flow=13, job_steps=13, peak=5, feasible=1, n_phases=4)),
+    # Over-estimated job waits.  Job 0 (o = 1, believed 4) sits out the slices 1 and 2.  Job 1
+    # (o = 3, believed 1) is killed after 1 round (phase 0: rounds 0..0) and after 2 more (phase 1:
+    # rounds 1..2).  Phase 2 (begins 3, slice 4) holds job 0 then job 1 in input order;
+    # k*(4, 0, 100) = 40 (Peak(40, 4, 0) = (160 + 4 + 40 - 4) / 2 = 100), offsets floor(4r / 40) = 0:
+    # both start at 3, completions 4 and 6.  Steps 1 + (1 + 2 + 3); peak = job 1's last round, 0 + 2 + 1.
+    dict(o=[1, 3], e=[4, 1], s=0, M=100, tau0=1, sched=O.SPS,
+         want=dict(flow=10, job_steps=7, peak=3, feasible=1, n_phases=3)),
+    # Simultaneous batches.  s = 2, M = 12, slices 2, 4, 8; batch size floor(12 / (2 + slice)) = 3, 2, 1.
+    # Phase 0 (slice 2): jobs 0, 1, 3 (believed 2, 2, 1) in one batch at round 0; job 1 (o = 1)
+    # completes at 1, jobs 0 (o = 3) and 3 (o = 5) are killed at 2.  Round 0 holds 3 x (2 + 0 + 1) = 9.
+    # Phase 1 (begins 2, slice 4): jobs 0 and 3 (job 2 believes 5 and waits), one batch at round 2;
+    # job 0 completes at 5, job 3 is killed at 6; round 4 holds (2 + 2 + 1) x 2 = 10, the peak.
+    # Phase 2 (begins 6, slice 8, one job per batch): job 2 at 6 completes at 8, job 3 at 14
+    # completes at 19.  Flow 1 + 5 + 8 + 19; steps (2 + 3) + 1 + 2 + (2 + 4 + 5).
+    dict(o=[3, 1, 2, 5], e=[2, 2, 5, 1], s=2, M=12, tau0=2, sched=O.SIMS,
+         want=dict(flow=33, job_steps=19, peak=10, feasible=1, n_phases=3)),
+    # Per-job prompts: the killed job carries its long prompt into the next phase.  M = 40, slices 2, 4.
+    # Phase 0: jobs 0 (s 1, o 2, believed 2) and 1 (s 10, o 4, believed 1); largest prompt 10,
+    # Peak(3, 2, 10) = 30 + (6 + 2 + 3 - 1) / 2 = 35 <= 40 < Peak(4, 2, 10), so k = 3 and both start at 0.
+    # Job 0 completes at 2, job 1 is killed at 2; round 1 holds (1 + 1 + 1) + (10 + 1 + 1) = 15.
+    # Phase 1 (begins 2): job 1, then job 2 (s 1, o 3, believed 4).  The largest prompt is still 10
+    # because job 1 is back: Peak(3, 4, 10) = 30 + (12 + 4 + 3 - 1) / 2 = 39 <= 40, k = 3 (with the
+    # prompt 1 of job 2 alone it would be 11 and job 2 would start a round earlier).  Offsets
+    # floor(4r / 3) = 0, 1: job 1 runs 2..5 and completes at 6, job 2 runs 3..5 and completes at 6.
+    # Round 5 holds (10 + 3 + 1) + (1 + 2 + 1) = 18.  Flow 2 + 6 + 6; steps 2 + (2 + 4) + 3.
+    dict(o=[2, 4, 3], e=[2, 1, 4], s=[1, 10, 1], M=40, tau0=2, sched=O.SPS,
+         want=dict(flow=14, job_steps=11, peak=18, feasible=1, n_phases=2)),
+]
+
+
+@pytest.mark.parametrize("case", HAND_ESTIMATE_CASES)
+def test_estimate_rule_hand_worked(case):
+    s = case["s"] if np.isscalar(case["s"]) else np.asarray(case["s"], np.int32)
+    got = O.gba_simulate(case["o"], s, case["M"], case["tau0"], case["sched"], o_est=case["e"])
+    assert got == case["want"]
+    # the second evaluator, on the same cases
+    ev = O.gba_simulate_batch(np.asarray([case["o"]], np.int32), s if np.isscalar(s) else s[None, :], case["M"],
+                              [(case["tau0"], case["sched"], 0, O.MODE_GBA)],
+                              np.asarray([case["e"]], np.int32), evaluator="events")
+    for key in ("flow", "job_steps", "peak", "feasible"):
+        assert int(ev[key][0, 0]) == case["want"][key], key
+
+
+# --------------------------------------------------------------------------
+# The second evaluator (start / end events) against the stepper
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(4))
+def test_event_evaluator_equals_the_stepper_on_random_instances(seed):
+    rng = np.random.default_rng(900 + seed)
+    for _ in range(150):
+        I, n = int(rng.integers(1, 4)), int(rng.integers(1, 120))
+        omax = int(rng.choice([1, 3, 40, 400]))
+        o = rng.integers(1, omax + 1, (I, n)).astype(np.int32)
+        hetero = bool(rng.integers(0, 2))
+        s = rng.integers(0, 60, (I, n)).astype(np.int32) if hetero else int(rng.integers(0, 60))
+        M = int(omax + 60 + rng.choice([0, 3, 500, 20000]))
+        e = np.maximum(1, np.rint(o * np.exp(rng.normal(0, 0.8, o.shape)))).astype(np.int32) \
+            if rng.integers(0, 2) else None
+        pts = [(int(rng.choice([1, 2, 3, 7, 16, 1000])), int(rng.integers(0, 2)),
+                int(rng.choice([0, 0, 1, 4, 1000])), int(rng.integers(0, 2))) for _ in range(4)]
+        a = O.gba_simulate_batch(o, s, M, pts, e)
+        b = O.gba_simulate_batch(o, s, M, pts, e, evaluator="events", threads=2)
+        for key in a:
+            assert np.array_equal(a[key], b[key]), (key, seed, n, pts)
+        lad = np.unique(rng.integers(1, 2 * omax + 2, 6)).astype(np.int32)
+        lad[-1] = max(lad[-1], omax, int(e.max()) if e is not None else 1)
+        for sched, k, mode in ((0, 0, 0), (1, 0, 1), (0, 3, 1)):
+            ee = None if e is None else e[0]
+            ss = s if np.isscalar(s) else s[0]
+            want = O.ladder_simulate(o[0], ss, M, lad, sched, k, mode, ee)
+            want.pop("n_phases")
+            assert O.events_ladder_simulate(o[0], ss, M, lad, sched, k, mode, ee) == want
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_event_evaluator_equals_the_stepper_on_the_workloads(cfg):
+    from paper_2601_22996_amd import workloads as W
+    w = W.WORKLOADS[cfg]
+    cnt = min(w.n_instances, 24 if cfg < 5 else 6)
+    d = W.generate(w, 0, cnt)
+    s = d["s"] if d["s"] is not None else d["s_scalar"]
+    a = O.gba_simulate_batch(d["o"], s, d["M"], w.sweep(), d["o_est"], threads=4)
+    b = O.gba_simulate_batch(d["o"], s, d["M"], w.sweep(), d["o_est"], threads=4, evaluator="events")
+    for key in a:
+        assert np.array_equal(a[key], b[key]), key
+    with pytest.raises(O.OracleError):
+        O.gba_simulate_batch(np.array([[5, 500]], np.int32), 10, 100, [(1, 0, 0, 0)], evaluator="events")
