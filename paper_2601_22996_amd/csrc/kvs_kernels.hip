@@ -178,9 +178,10 @@ __device__ __forceinline__ JobView view_job(const RawJob &r, const JobsDev &J, c
     return v;
 }
 
-/* 768 threads: two workgroups per compute unit need 6 wavefronts per SIMD, i.e. at most 80 VGPRs. */
+/* One instance at the points of one launch, by one workgroup of T threads. */
 template <int T, bool PACKED, bool NESTED, int WIN, int LV, int HOLD>
-__global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDev J, GroupArg G, OutsDev out)
+__device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg &G, const OutsDev &out,
+                                               const uint32_t inst)
 {
     constexpr int NW = T / 64;
     constexpr int kLevels = LV;          /* levels of the ladder this instantiation can hold */
@@ -208,7 +209,6 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const uint32_t inst = blockIdx.x;
     const uint32_t n = (uint32_t)J.n_jobs;
     const size_t row = (size_t)inst * n;
     const bool per_job_s = (J.s != nullptr);
@@ -218,12 +218,6 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
     const bool with_estimates = !NESTED && mode == MODE_GBA && J.e != nullptr;
     const bool one_phase_each = NESTED || (mode == MODE_GBA && J.e == nullptr);
     const uint32_t m_min = G.m[0];
-
-    if (!PACKED) {
-        /* only the instances the one-word kernel left behind */
-        if (out.feasible[(size_t)G.pt_q[0] * (size_t)J.n_inst + inst] != FEASIBLE_PENDING)
-            return;
-    }
 
     /* each wavefront owns a contiguous segment of the jobs */
     const uint32_t seg = ((n + NW - 1) / NW + 255u) & ~255u; /* whole 256-job chunks */
@@ -483,13 +477,16 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
                 done += totL[l];
                 sm = sMaxEnter[l] > sm ? sMaxEnter[l] : sm;
                 if (l < lv)
-                    below += totE[l];
+                    below += totL[l]; /* jobs that are through before level lv */
             }
             sl.n = enter;
             sl.done = done;
             if (per_job_s)
                 sl.smax = sm;
-            /* nobody from below: the merged phase is the level's own phase */
+            /* Nobody is through below this level: everyone who has entered by now is still there,
+             * so the merged phase holds exactly the jobs of the level's own phase, and the same of
+             * them complete.  (One phase per job: nobody enters below.  Algorithm 1: no job is
+             * shorter than the slice below.) */
             if (mode != MODE_SINGLE && lv > m_min && below == 0)
                 sl.alias = lv;
         }
@@ -965,6 +962,40 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
     }
 }
 
+/* Workgroups of the kernel with two-word entries: each looks after the instances
+ * blockIdx.x, blockIdx.x + kWideGrid, ... and works on those the one-word kernel left behind. */
+constexpr uint32_t kWideGrid = 1024;
+
+/* 768 threads: two workgroups per compute unit need 6 wavefronts per SIMD, i.e. at most 80 VGPRs. */
+template <int T, bool PACKED, bool NESTED, int WIN, int LV, int HOLD>
+__global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDev J, GroupArg G, OutsDev out)
+{
+    if (PACKED) { /* one workgroup per instance */
+        sweep_instance<T, PACKED, NESTED, WIN, LV, HOLD>(J, G, out, blockIdx.x);
+        return;
+    }
+    /* Two-word entries: only the instances that the one-word kernel marked in `feasible`, usually
+     * none.  64 of the workgroup's instances at a time: every wavefront reads the same 64 marks
+     * (lane l the mark of the l-th of them) and so arrives at the same list, then all work
+     * through it together.  A mark is overwritten only by this workgroup, at the end of that
+     * instance's evaluation, which no wavefront reaches before all have read the marks (the
+     * evaluation takes workgroup barriers on the way). */
+    const uint32_t n_inst = (uint32_t)J.n_inst;
+    const int lane = threadIdx.x & 63;
+    for (uint32_t first = blockIdx.x; first < n_inst; first += 64u * gridDim.x) {
+        const uint64_t cand = (uint64_t)first + (uint64_t)lane * gridDim.x;
+        const bool pending = cand < n_inst &&
+                             out.feasible[(size_t)G.pt_q[0] * (size_t)n_inst + (size_t)cand] == FEASIBLE_PENDING;
+        uint64_t todo = __ballot(pending);
+        while (todo) {
+            const uint32_t j = (uint32_t)__ffsll((unsigned long long)todo) - 1u;
+            todo &= todo - 1u;
+            sweep_instance<T, PACKED, NESTED, WIN, LV, HOLD>(J, G, out, first + j * gridDim.x);
+            __syncthreads(); /* the tables in LDS are set up afresh for the next instance */
+        }
+    }
+}
+
 /* ---- input scan for kvs_validate ---- */
 struct ValidateResult {
     uint32_t bad_value;  /* o < 1, s < 0 or o_est < 1 */
@@ -1082,7 +1113,9 @@ int32_t launch_sweep(const JobsDev &J, const GroupArg &G, const OutsDev &out, hi
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return KVS_EHIP;
-    hipLaunchKernelGGL(kern, dim3((uint32_t)J.n_inst), dim3(T), lds, st, J, G, out);
+    const uint32_t grid = PACKED ? (uint32_t)J.n_inst
+                                 : ((uint32_t)J.n_inst < kWideGrid ? (uint32_t)J.n_inst : kWideGrid);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(T), lds, st, J, G, out);
     return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
 }
 
