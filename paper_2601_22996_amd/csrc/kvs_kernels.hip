@@ -35,6 +35,7 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 
 #include "kvsched.h"
@@ -59,6 +60,23 @@ constexpr uint8_t FEASIBLE_PENDING = 0xFD; /* internal: left for the two-word-en
 
 constexpr int MODE_GBA = 0, MODE_GSA = 1, MODE_SINGLE = 2;
 
+/*
+ * The instantiations of the evaluation kernel, by how the jobs get into phase order in LDS.
+ *   NESTED  every job has one phase (Algorithm 2 on true lengths): a copy of the instance
+ *           is cut into the phases by stable partitions inside LDS;
+ *   ALIVE   every job is tried in every phase until it completes (Algorithm 1, and a lone
+ *           invocation of the subroutine): the unfinished jobs stay in LDS in input order,
+ *           phases are evaluated from that list and the completed jobs are taken out of it;
+ *   GATHER  classes by estimates: the instance stays in LDS beside the phase buffer and the
+ *           phases are gathered from it, as many at a time as the buffer holds;
+ *   STREAM  the same, gathered from memory (instances too large for two copies in LDS
+ *           beside a second workgroup);
+ *   WIDE    two-word entries, every phase compacted from memory: whatever the others
+ *           leave behind because a value is too wide for their one-word entries.
+ * The first four read the jobs from memory once (STREAM: once per batch of phases).
+ */
+constexpr int KIND_NESTED = 0, KIND_ALIVE = 1, KIND_GATHER = 2, KIND_STREAM = 3, KIND_WIDE = 4;
+
 struct JobsDev {
     const int32_t *o;
     const int32_t *s;
@@ -67,6 +85,7 @@ struct JobsDev {
     int32_t n_jobs;
     uint32_t s_scalar;
     uint32_t vec4; /* rows are 16-byte aligned and n_jobs is a multiple of 4: 128-bit loads allowed */
+    uint32_t wide_all; /* two-word kernel: every instance is its to do, not only the marked ones   */
     uint64_t M;
 };
 
@@ -179,7 +198,7 @@ __device__ __forceinline__ JobView view_job(const RawJob &r, const JobsDev &J, c
 }
 
 /* One instance at the points of one launch, by one workgroup of T threads. */
-template <int T, bool PACKED, bool NESTED, int WIN, int LV, int HOLD>
+template <int T, int KIND, int WIN, int LV, int HOLD>
 __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg &G, const OutsDev &out,
                                                const uint32_t inst)
 {
@@ -188,9 +207,16 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
     constexpr int kSlots = LV + kMaxM;   /* phase slots: one per level, one per merged first phase */
     constexpr bool EXPLICIT = (LV == kLevelsMax); /* explicit ladders get the large instantiation */
     static_assert(LV == kLevelsGeo || LV == kLevelsMax, "levels");
-    static_assert(PACKED || !NESTED, "the LDS-only path works on one-word entries");
+    constexpr bool PACKED = KIND != KIND_WIDE;   /* one-word entries */
+    constexpr bool NESTED = KIND == KIND_NESTED;
+    constexpr bool ALIVE = KIND == KIND_ALIVE;
+    constexpr bool GATHERS = KIND == KIND_GATHER || KIND == KIND_STREAM;
+    constexpr bool COPY = KIND == KIND_GATHER;   /* the instance is kept in LDS beside the phase buffer */
 
-    extern __shared__ uint32_t buf[]; /* phase entries: n_jobs words, twice that when !PACKED */
+    /* Dynamic LDS.  Phase entries: n_jobs words, twice that when !PACKED.  COPY: behind them
+     * the instance in input order, one word per job (prompt << 16 | length with per-job prompts,
+     * else the length), and behind that one byte per job for its entry level. */
+    extern __shared__ uint32_t buf[];
 
     static_assert(WIN % 64 == 0 && WIN <= kWinMax, "window size");
     __shared__ unsigned long long ev[NW][WIN];
@@ -203,6 +229,9 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
     __shared__ Sched sched[kMaxV][kSlots];
     __shared__ Result res[kMaxV][kSlots];
     __shared__ uint32_t wkeep[NW]; /* per wavefront: entries its stretch keeps in a partition */
+    __shared__ uint8_t order[kSlots];      /* GATHERS: the slots to evaluate, batch after batch */
+    __shared__ uint8_t bstart[kSlots + 1]; /* ... batch b is order[bstart[b] .. bstart[b + 1])  */
+    __shared__ uint32_t n_batches;
     __shared__ unsigned long long sumO_sh;
     __shared__ uint32_t flags, maxO_sh, maxS_sh, maxE_sh;
 
@@ -214,10 +243,16 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
     const bool per_job_s = (J.s != nullptr);
     /* the one-phase instantiation is launched only for GBA on true lengths: saying so here lets
      * the compiler drop the other modes from it */
-    const int mode = NESTED ? MODE_GBA : (int)G.mode;
-    const bool with_estimates = !NESTED && mode == MODE_GBA && J.e != nullptr;
-    const bool one_phase_each = NESTED || (mode == MODE_GBA && J.e == nullptr);
+    /* what the host launches an instantiation for is said here, so that the compiler drops the
+     * other modes from it */
+    const int mode = (NESTED || GATHERS) ? MODE_GBA
+                     : ALIVE ? ((int)G.mode == MODE_SINGLE ? MODE_SINGLE : MODE_GSA)
+                             : (int)G.mode;
+    const bool with_estimates = GATHERS || (!PACKED && mode == MODE_GBA && J.e != nullptr);
+    const bool one_phase_each = NESTED || (!PACKED && mode == MODE_GBA && J.e == nullptr);
     const uint32_t m_min = G.m[0];
+    uint32_t *const jobs_lds = buf + n;                                /* COPY only */
+    uint8_t *const ga_lds = reinterpret_cast<uint8_t *>(buf + 2u * n); /* COPY only */
 
     /* each wavefront owns a contiguous segment of the jobs */
     const uint32_t seg = ((n + NW - 1) / NW + 255u) & ~255u; /* whole 256-job chunks */
@@ -251,17 +286,25 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
     {
         /* Most jobs fall into two or three levels, and lanes that add to the same counter are
          * served one after the other.  The wavefront's window, idle until phases are evaluated,
-         * holds kRep copies of the entry histogram, one per group of lanes (rows one word longer
-         * than the levels, so equal levels of different copies sit in different banks). */
+         * holds kRep copies of a level histogram, one per group of lanes (rows one word longer
+         * than the levels, so equal levels of different copies sit in different banks): the
+         * entry levels, or the levels at which the jobs complete where everybody enters at once
+         * (ALIVE).  Where both differ from job to job (GATHERS) a second histogram with fewer
+         * copies behind the first takes the completion levels. */
         constexpr int kRowE = kLevels + 1;
         constexpr int kRep = (2 * WIN / kRowE >= 8) ? 8 : (2 * WIN / kRowE >= 4) ? 4 : (2 * WIN / kRowE >= 2) ? 2 : 1;
         static_assert(kRep * kRowE <= 2 * WIN, "histogram copies fit the window");
+        constexpr int kRoom2 = (2 * WIN - kRep * kRowE) / kRowE;
+        constexpr int kRep2 = kRoom2 >= 4 ? 4 : kRoom2 >= 2 ? 2 : 1;
+        static_assert(!GATHERS || kRoom2 >= 1, "the second histogram fits the window");
         uint32_t *histE = reinterpret_cast<uint32_t *>(ev[wave]);
-        for (int i = lane; i < kRep * kRowE; i += 64)
+        uint32_t *histL = histE + kRep * kRowE;
+        for (int i = lane; i < (kRep + (GATHERS ? kRep2 : 0)) * kRowE; i += 64)
             histE[i] = 0;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         uint32_t *myE = histE + (lane & (kRep - 1)) * kRowE;
+        uint32_t *myL = histL + (lane & (kRep2 - 1)) * kRowE;
         unsigned long long sumO = 0;
         uint32_t mxO = 0, mxS = 0, mxG = 0;
         uint32_t badbits = 0;
@@ -275,15 +318,22 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
             mxS = v.s > mxS ? v.s : mxS;
             if (!NESTED) /* only the entry format of the other instantiations asks for it */
                 mxG = v.gb > mxG ? v.gb : mxG;
-            if (NESTED) /* the job as a phase entry, at its place in the input */
+            if (NESTED || ALIVE) /* the job as a phase entry (ALIVE: with its whole length), at its place in the input */
                 buf[i] = per_job_s ? ((v.s << 16) | (v.o & 0xffffu)) : v.o;
-            atomicAdd(&myE[v.ga], 1u); /* the wavefront's own histogram */
-            if (!one_phase_each)
+            if (COPY) { /* the job itself, at its place in the input */
+                jobs_lds[i] = per_job_s ? ((v.s << 16) | (v.o & 0xffffu)) : v.o;
+                ga_lds[i] = (uint8_t)v.ga;
+            }
+            const uint32_t g_max = ALIVE ? v.gb : v.ga; /* the level that keeps this job's prompt */
+            atomicAdd(&myE[g_max], 1u); /* the wavefront's own histogram */
+            if (GATHERS)
+                atomicAdd(&myL[v.gb], 1u);
+            else if (!PACKED && !one_phase_each)
                 atomicAdd(&cumL[wave][v.gb], 1u);
             if (per_job_s) { /* the maxima settle after a few jobs; then this only reads */
-                if (v.s > sMaxEnter[v.ga])
-                    atomicMax(&sMaxEnter[v.ga], v.s);
-                if (!NESTED) /* one phase per job: the levels it takes part in are the one it enters */
+                if (v.s > sMaxEnter[g_max])
+                    atomicMax(&sMaxEnter[g_max], v.s);
+                if (!NESTED && !ALIVE) /* else one level says it all: the only one (NESTED), the last one (ALIVE) */
                     for (uint32_t l = v.ga; l <= v.gb; l++)
                         if (v.s > sMaxPart[l])
                             atomicMax(&sMaxPart[l], v.s);
@@ -336,11 +386,20 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        uint32_t cntE = 0;
-        if (lane < kLevels)
+        uint32_t cntE = 0, cntL = 0;
+        if (lane < kLevels) {
             for (int r = 0; r < kRep; r++)
                 cntE += histE[r * kRowE + lane];
-        const uint32_t cntL = one_phase_each ? cntE : ((lane < kLevels) ? cumL[wave][lane] : 0u);
+            if (GATHERS)
+                for (int r = 0; r < kRep2; r++)
+                    cntL += histL[r * kRowE + lane];
+            else if (!PACKED && !one_phase_each)
+                cntL = cumL[wave][lane];
+            else
+                cntL = cntE;
+        }
+        if (ALIVE) /* counted: the levels of completion; everybody enters at level 0 */
+            cntE = (lane == 0) ? seg_hi - seg_lo : 0u;
         /* inclusive prefix over levels (lanes 0..31 hold the levels) */
         uint32_t pe = cntE, pl = cntL;
 #pragma unroll
@@ -389,6 +448,12 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
         }
         totE[tid] = e;
         totL[tid] = l;
+        if (ALIVE && per_job_s) { /* a level's phase holds the jobs that complete there or later */
+            uint32_t m = 0;
+            for (int g = tid; g < kLevels; g++)
+                m = sMaxEnter[g] > m ? sMaxEnter[g] : m;
+            sMaxPart[tid] = m;
+        }
     }
     __syncthreads();
 
@@ -397,19 +462,20 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
      * 16 bits under a 16-bit prompt, or a bare duration): every phase's entries are then cut out
      * of that copy inside LDS and the jobs are not read from memory again. */
     constexpr bool nested = NESTED; /* launched only when every job has one phase (no estimates, GBA) */
-    if (NESTED && per_job_s && (maxO_sh >= 65536u || maxS_sh >= 65536u) && flags == 0) {
+    if ((NESTED || ALIVE || COPY) && per_job_s && (maxO_sh >= 65536u || maxS_sh >= 65536u) && flags == 0) {
         /* too wide for the copy: left to the kernel with two-word entries */
         if (tid < G.n_pts)
             out.feasible[(size_t)G.pt_q[tid] * (size_t)J.n_inst + inst] = FEASIBLE_PENDING;
         return;
     }
     EntryFmt F;
-    if (nested) {
+    F.raw = ALIVE;
+    if (nested || ALIVE) {
         F.dbits = per_job_s ? 16u : 31u;
         F.sshift = F.dbits;
         F.has_s = per_job_s;
         F.swidth = per_job_s ? 16u : 0u;
-        F.all_done = true;
+        F.all_done = nested;
     } else {
         /* durations are at most max(o), or a slice of a level some job reaches */
         uint64_t dmax = lad[maxE_sh];
@@ -482,7 +548,7 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
             sl.n = enter;
             sl.done = done;
             if (per_job_s)
-                sl.smax = sm;
+                sl.smax = ALIVE ? maxS_sh : sm; /* ALIVE: everybody is in a first phase */
             /* Nobody is through below this level: everyone who has entered by now is still there,
              * so the merged phase holds exactly the jobs of the level's own phase, and the same of
              * them complete.  (One phase per job: nobody enters below.  Algorithm 1: no job is
@@ -669,14 +735,102 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
         }
     };
 
+    /*
+     * GATHERS: the entries of the slots order[b0 .. b1) gathered from the copy of the instance
+     * in LDS (or from memory), every slot's participants in input order at its own place in the
+     * phase buffer.  A job takes part in the level slots from the level at which it enters to
+     * the one at which it completes, and in the merged first phase of every shift at or above
+     * its entry level.  Each wavefront walks its own segment of the jobs (the one it counted in
+     * pass 1, so the per-wavefront counts tell where its entries of a slot begin); lane j keeps
+     * what the wavefront needs to know about the j-th slot of the batch.  For every 64 jobs the
+     * levels that any of them takes part in are or-ed into one mask, and only the batch's slots
+     * at those levels are gone through.
+     */
+    auto gather = [&](uint32_t b0, uint32_t b1) {
+        const uint32_t g_cnt = b1 - b0; /* at most 64 */
+        uint32_t my_lv = 0, my_level = 0, my_tau = 0, my_below = 0, my_cur = 0;
+        if ((uint32_t)lane < g_cnt) {
+            const uint32_t si = order[b0 + (uint32_t)lane];
+            my_level = si < (uint32_t)kLevels ? 1u : 0u;
+            my_lv = my_level ? si : (uint32_t)G.m[si - kLevels];
+            my_tau = lad[my_lv];
+            my_below = my_lv ? lad[my_lv - 1u] : 0u;
+            my_cur = slot[si].off;
+            for (int w = 0; w < wave; w++) {
+                uint32_t c = cumE[w][my_lv];
+                if (my_level && my_lv > 0)
+                    c -= cumL[w][my_lv - 1u];
+                my_cur += c;
+            }
+        }
+        RawJob nxt;
+        nxt.o = nxt.s = nxt.e = 1;
+        if (!COPY && seg_lo + lane < seg_hi)
+            nxt = load_job(J, row + seg_lo + lane, true);
+        for (uint32_t base = seg_lo; base < seg_hi; base += 64) {
+            const uint32_t i = base + (uint32_t)lane;
+            const bool act = i < seg_hi;
+            uint32_t o, s, ga;
+            if (COPY) {
+                const uint32_t w = act ? jobs_lds[i] : 0u;
+                o = per_job_s ? (w & 0xffffu) : w;
+                s = per_job_s ? (w >> 16) : J.s_scalar;
+                ga = act ? (uint32_t)ga_lds[i] : 0u;
+            } else {
+                const RawJob raw = nxt;
+                if (i + 64 < seg_hi)
+                    nxt = load_job(J, row + i + 64, true);
+                const JobView v = view_job<EXPLICIT>(raw, J, G, lad, mode, true);
+                o = v.o;
+                s = v.s;
+                ga = v.ga;
+            }
+            /* lowest entry level among these jobs (a merged phase below it gets none of them) and
+             * the levels at which some of them is still unfinished: a job that enters at ga and
+             * has the length o is there at the levels ga .. max(ga, level of o) */
+            uint64_t here; /* bit l: some job takes part at level l; its lowest bit: the lowest entry level */
+            {
+                bool ok = true; /* checked in pass 1 */
+                const uint32_t go = act ? level_of<EXPLICIT>(o, G, lad, ok) : 0u;
+                const uint32_t gb = go > ga ? go : ga;
+                const uint64_t mine =
+                    act ? (((gb >= 63u) ? ~0ull : ((2ull << gb) - 1ull)) & ~((1ull << ga) - 1ull)) : 0ull;
+                here = (uint64_t)wave_or((uint32_t)mine);
+                if (kLevels > 32)
+                    here |= (uint64_t)wave_or((uint32_t)(mine >> 32)) << 32;
+            }
+            const uint32_t ga_min = here ? (uint32_t)__builtin_ctzll(here) : 0xffffffffu;
+            for (uint32_t j = 0; j < g_cnt; j++) {
+                const uint32_t lv = __builtin_amdgcn_readlane(my_lv, (int)j);
+                const uint32_t level = __builtin_amdgcn_readlane(my_level, (int)j);
+                if (level ? !((here >> lv) & 1ull) : (ga_min > lv))
+                    continue; /* none of these jobs is in that phase */
+                const uint32_t tau_lv = __builtin_amdgcn_readlane(my_tau, (int)j);
+                const uint32_t tau_below = __builtin_amdgcn_readlane(my_below, (int)j);
+                /* entered by now; and, for a level's own phase, not through before it */
+                const bool take = act && ga <= lv && (!level || ga == lv || o > tau_below);
+                const uint64_t bal = __ballot(take);
+                if (bal == 0)
+                    continue;
+                const uint32_t at = __builtin_amdgcn_readlane(my_cur, (int)j);
+                if (take) {
+                    const bool done = o <= tau_lv;
+                    put_entry<PACKED>(buf, n, at + lanes_below(bal), done ? o : tau_lv, done, s, F);
+                }
+                if ((uint32_t)lane == j)
+                    my_cur += (uint32_t)__popcll(bal);
+            }
+        }
+    };
+
     /* Chunks of 64 entries a wavefront holds in registers while LDS is rearranged under it. */
     constexpr int kHold = HOLD; /* the launch guarantees n_jobs <= HOLD * T */
     const uint32_t dmask = (F.dbits >= 32u) ? 0xffffffffu : ((1u << F.dbits) - 1u);
 
     /* Stable partition of buf[0 .. cnt): entries with duration <= theta keep their order at
-     * the front, the others follow, also in order.  Each wavefront takes a stretch, holds it
+     * the front, the others follow, also in order (long_first: the other way round).  Each wavefront takes a stretch, holds it
      * in registers across the barrier and writes it back to its two destinations. */
-    auto split_front = [&](uint32_t cnt, uint32_t theta) {
+    auto split_front = [&](uint32_t cnt, uint32_t theta, bool long_first = false) {
         const uint32_t span = ((cnt + NW - 1) / NW + 63u) & ~63u;
         const uint32_t lo = (uint32_t)wave * span < cnt ? (uint32_t)wave * span : cnt;
         const uint32_t hi = lo + span < cnt ? lo + span : cnt;
@@ -688,7 +842,7 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                 break; /* the rest of the stretch is empty (the same for all lanes) */
             const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
             held[c] = (idx < hi) ? buf[idx] : 0xffffffffu;
-            const bool keep = idx < hi && (held[c] & dmask) <= theta;
+            const bool keep = idx < hi && ((held[c] & dmask) <= theta) != long_first;
             kept += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(keep));
         }
         if (lane == 0)
@@ -713,7 +867,7 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
             /* the entries of a chunk sit in its first lanes, so a lane's rank among them is its
              * number, and its rank among the moved ones is that minus its rank among the kept */
             const bool act = at + (uint32_t)lane < hi;
-            const bool keep = act && (held[c] & dmask) <= theta;
+            const bool keep = act && ((held[c] & dmask) <= theta) != long_first;
             const uint64_t bk = __builtin_amdgcn_ballot_w64(keep);
             const uint32_t rk = lanes_below(bk);
             if (act)
@@ -783,7 +937,70 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
         __syncthreads();
     };
 
-    if (!bad) {
+    if (ALIVE) {
+        if (!bad) {
+            /* ---- the list of unfinished jobs, in input order, is the phase ---- */
+            /* first phases: everybody, whatever the shift (none of them moves the list) */
+            for (int mi = 0; mi < (int)G.n_m; mi++)
+                eval_slot(kLevels + mi);
+            uint32_t cnt = n;   /* jobs in the list */
+            uint32_t alive = n; /* of which are unfinished when the next level begins */
+            for (uint32_t l = 0; l <= m_min; l++)
+                alive -= totL[l];
+            for (int si = (int)m_min + 1; si < kLevels && mode != MODE_SINGLE; si++) {
+                const uint32_t left = alive; /* the jobs longer than the slice below */
+                if (left == 0)
+                    break;
+                alive -= totL[si];
+                if (left < cnt) {
+                    __syncthreads(); /* the phases evaluated so far have read the list */
+                    split_front(cnt, lad[si - 1], true);
+                    cnt = left;
+                }
+                eval_slot(si);
+            }
+            __syncthreads();
+        }
+    } else if (GATHERS) {
+      if (!bad) {
+        /* ---- batches of slots: as many as the phase buffer holds, gathered, then evaluated ---- */
+        if (tid == 0) {
+            uint32_t nb = 0, cnt = 0, used = 0, fill = 0;
+            bstart[0] = 0;
+            auto add = [&](int si) {
+                const uint32_t ns = slot[si].n;
+                if (ns == 0 || slot[si].alias != (uint32_t)si)
+                    return;
+                if (fill + ns > n || cnt - bstart[nb] >= 64u) { /* the buffer or the lanes are full */
+                    bstart[++nb] = (uint8_t)cnt;
+                    fill = 0;
+                }
+                slot[si].off = fill;
+                fill += ns;
+                order[cnt++] = (uint8_t)si;
+                used = 1;
+            };
+            if (mode != MODE_SINGLE)
+                for (int si = (int)m_min + 1; si < kLevels; si++)
+                    add(si);
+            for (int mi = 0; mi < (int)G.n_m; mi++)
+                add(kLevels + mi);
+            if (used)
+                bstart[++nb] = (uint8_t)cnt;
+            n_batches = nb;
+        }
+        __syncthreads();
+        const uint32_t nb = n_batches;
+        for (uint32_t b = 0; b < nb; b++) {
+            const uint32_t b0 = bstart[b], b1 = bstart[b + 1];
+            gather(b0, b1);
+            __syncthreads();
+            for (uint32_t j = b0; j < b1; j++)
+                eval_slot((int)order[j]);
+            __syncthreads();
+        }
+      }
+    } else if (!bad) {
         if (nested) {
 /* ---- every phase is cut out of the LDS copy of the instance ---- */
             const uint32_t m_max = G.m[G.n_m - 1];
@@ -967,11 +1184,11 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
 constexpr uint32_t kWideGrid = 1024;
 
 /* 768 threads: two workgroups per compute unit need 6 wavefronts per SIMD, i.e. at most 80 VGPRs. */
-template <int T, bool PACKED, bool NESTED, int WIN, int LV, int HOLD>
+template <int T, int KIND, int WIN, int LV, int HOLD>
 __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDev J, GroupArg G, OutsDev out)
 {
-    if (PACKED) { /* one workgroup per instance */
-        sweep_instance<T, PACKED, NESTED, WIN, LV, HOLD>(J, G, out, blockIdx.x);
+    if (KIND != KIND_WIDE) { /* one workgroup per instance */
+        sweep_instance<T, KIND, WIN, LV, HOLD>(J, G, out, blockIdx.x);
         return;
     }
     /* Two-word entries: only the instances that the one-word kernel marked in `feasible`, usually
@@ -985,12 +1202,13 @@ __global__ __launch_bounds__(T, (T == 768 ? 6 : 1)) void kvs_sweep_kernel(JobsDe
     for (uint32_t first = blockIdx.x; first < n_inst; first += 64u * gridDim.x) {
         const uint64_t cand = (uint64_t)first + (uint64_t)lane * gridDim.x;
         const bool pending = cand < n_inst &&
-                             out.feasible[(size_t)G.pt_q[0] * (size_t)n_inst + (size_t)cand] == FEASIBLE_PENDING;
+                             (J.wide_all ||
+                              out.feasible[(size_t)G.pt_q[0] * (size_t)n_inst + (size_t)cand] == FEASIBLE_PENDING);
         uint64_t todo = __ballot(pending);
         while (todo) {
             const uint32_t j = (uint32_t)__ffsll((unsigned long long)todo) - 1u;
             todo &= todo - 1u;
-            sweep_instance<T, PACKED, NESTED, WIN, LV, HOLD>(J, G, out, first + j * gridDim.x);
+            sweep_instance<T, KIND, WIN, LV, HOLD>(J, G, out, first + j * gridDim.x);
             __syncthreads(); /* the tables in LDS are set up afresh for the next instance */
         }
     }
@@ -1101,53 +1319,78 @@ JobsDev to_dev(const kvs_jobs_t *jobs, bool use_estimates)
     const uintptr_t bits = reinterpret_cast<uintptr_t>(J.o) | reinterpret_cast<uintptr_t>(J.s) |
                            reinterpret_cast<uintptr_t>(J.e);
     J.vec4 = (jobs->n_jobs % 4 == 0 && bits % 16 == 0) ? 1u : 0u;
+    J.wide_all = 0;
     return J;
 }
 
-template <int T, bool PACKED, bool NESTED, int WIN, int LV, int HOLD>
+constexpr int32_t kNoRoom = -1;          /* internal: the instantiation's LDS need exceeds the compute unit's */
+constexpr size_t kLdsPerGroup = 160 * 1024; /* LDS a workgroup can have on gfx950 */
+
+template <int T, int KIND, int WIN, int LV, int HOLD>
 int32_t launch_sweep(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
 {
-    const size_t lds = sizeof(uint32_t) * (size_t)J.n_jobs * (PACKED ? 1 : 2);
-    static_assert(!NESTED || HOLD * T >= (T == 256 ? 4096 : 1), "hold");
-    auto kern = kvs_sweep_kernel<T, PACKED, NESTED, WIN, LV, HOLD>;
+    /* phase entries; GATHER: also the instance itself, one word and one byte per job */
+    const size_t n = (size_t)J.n_jobs;
+    size_t lds = sizeof(uint32_t) * n * (KIND == KIND_WIDE ? 2 : 1);
+    if (KIND == KIND_GATHER)
+        lds += sizeof(uint32_t) * n + ((n + 3) & ~(size_t)3);
+    static_assert((KIND != KIND_NESTED && KIND != KIND_ALIVE) || HOLD * T >= (T == 256 ? 4096 : 1), "hold");
+    auto kern = kvs_sweep_kernel<T, KIND, WIN, LV, HOLD>;
+    static std::atomic<int> static_lds{-1}; /* of this instantiation; the same on every device */
+    int fixed = static_lds.load(std::memory_order_relaxed);
+    if (fixed < 0) {
+        hipFuncAttributes attr;
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(kern)) != hipSuccess)
+            return KVS_EHIP;
+        fixed = (int)attr.sharedSizeBytes;
+        static_lds.store(fixed, std::memory_order_relaxed);
+    }
+    if (lds + (size_t)fixed > kLdsPerGroup)
+        return kNoRoom;
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return KVS_EHIP;
-    const uint32_t grid = PACKED ? (uint32_t)J.n_inst
+    const uint32_t grid = KIND != KIND_WIDE ? (uint32_t)J.n_inst
                                  : ((uint32_t)J.n_inst < kWideGrid ? (uint32_t)J.n_inst : kWideGrid);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(T), lds, st, J, G, out);
     return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
 }
 
 /*
- * First launch: one-word entries.  When every job has exactly one phase (GBA on true
- * lengths) the instantiation that cuts all phases out of one LDS copy, else the one that
- * compacts each phase from memory.  Second launch, only with per-job prompts: the instances
- * the first one marked as too wide, with two-word entries.
+ * First launch: one-word entries, the instantiation that fits the mode (see the list of
+ * kinds above).  Second launch, only with per-job prompts: the instances the first one marked
+ * as too wide, with two-word entries, every phase compacted from memory; it also takes every
+ * instance should the first launch's LDS need ever exceed a compute unit's.
  */
 template <int LV>
 int32_t run_group_lv(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)
 {
     int32_t rc;
     const bool big = J.n_jobs > 4096;
-    const bool one_phase_each = (G.mode == MODE_GBA) && (J.e == nullptr);
     /* registers a thread needs to hold its share of an instance: n_jobs / threads, rounded up */
     constexpr int kHoldMid = 14, kHoldMax = (KVS_MAX_JOBS + 767) / 768;
     const bool mid = J.n_jobs <= kHoldMid * 768;
     /* Large instances: 12 wavefronts and 256-round windows keep two workgroups (24 wavefronts)
      * on a compute unit next to a 40 KB phase buffer; measured best among the shapes tried. */
-    if (one_phase_each)
-        rc = !big ? launch_sweep<256, true, true, 256, LV, 16>(J, G, out, st)
-             : mid ? launch_sweep<768, true, true, 256, LV, kHoldMid>(J, G, out, st)
-                   : launch_sweep<768, true, true, 256, LV, kHoldMax>(J, G, out, st);
-    else
-        rc = !big ? launch_sweep<256, true, false, 256, LV, 1>(J, G, out, st)
-                  : launch_sweep<768, true, false, 256, LV, 1>(J, G, out, st);
-    if (rc != KVS_OK || !J.s)
+    if (G.mode == MODE_GBA && J.e == nullptr) /* one phase per job */
+        rc = !big ? launch_sweep<256, KIND_NESTED, 256, LV, 16>(J, G, out, st)
+             : mid ? launch_sweep<768, KIND_NESTED, 256, LV, kHoldMid>(J, G, out, st)
+                   : launch_sweep<768, KIND_NESTED, 256, LV, kHoldMax>(J, G, out, st);
+    else if (G.mode != MODE_GBA) /* everybody in every phase until done */
+        rc = !big ? launch_sweep<256, KIND_ALIVE, 256, LV, 16>(J, G, out, st)
+             : mid ? launch_sweep<768, KIND_ALIVE, 256, LV, kHoldMid>(J, G, out, st)
+                   : launch_sweep<768, KIND_ALIVE, 256, LV, kHoldMax>(J, G, out, st);
+    else /* classes by estimates: two copies in LDS while several workgroups still share a compute unit */
+        rc = !big ? launch_sweep<256, KIND_GATHER, 256, LV, 1>(J, G, out, st)
+                  : launch_sweep<768, KIND_STREAM, 256, LV, 1>(J, G, out, st);
+    JobsDev J2 = J;
+    if (rc == kNoRoom)
+        J2.wide_all = 1;
+    else if (rc != KVS_OK || !J.s)
         return rc;
     constexpr int kWinBig = (LV == kLevelsMax) ? 128 : 256; /* 16384 two-word entries fill most of LDS */
-    return big ? launch_sweep<512, false, false, kWinBig, LV, 1>(J, G, out, st)
-               : launch_sweep<256, false, false, 256, LV, 1>(J, G, out, st);
+    return big ? launch_sweep<512, KIND_WIDE, kWinBig, LV, 1>(J2, G, out, st)
+               : launch_sweep<256, KIND_WIDE, 256, LV, 1>(J2, G, out, st);
 }
 
 int32_t run_group(const JobsDev &J, const GroupArg &G, const OutsDev &out, hipStream_t st)

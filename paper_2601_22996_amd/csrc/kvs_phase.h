@@ -87,6 +87,8 @@ struct EntryFmt {
     uint32_t s_add;  /* the common prompt length when none is stored, else 0                  */
     bool has_s;      /* per-job prompts are stored at all                                     */
     bool all_done;   /* every run completes: no done-bit                                      */
+    bool raw;        /* the duration field holds the job's whole length: the run completes if
+                        that is within the slice and is cut off at the slice otherwise         */
 };
 
 template <bool PACKED>
@@ -109,12 +111,17 @@ __device__ __forceinline__ void put_entry(uint32_t *buf, uint32_t n_cap, uint32_
 template <bool PACKED>
 __device__ __forceinline__ void get_entry(const uint32_t *buf, uint32_t n_cap, uint32_t pos,
                                           uint32_t &d, bool &done, uint32_t &s, uint32_t s_scalar,
-                                          const EntryFmt &F)
+                                          const EntryFmt &F, uint32_t tau)
 {
     const uint32_t w = buf[pos];
     if (PACKED) {
         d = w & ((1u << F.dbits) - 1u);
-        done = F.all_done || ((w >> F.dbits) & 1u);
+        if (F.raw) {
+            done = d <= tau;
+            d = done ? d : tau;
+        } else {
+            done = F.all_done || ((w >> F.dbits) & 1u);
+        }
         s = __builtin_amdgcn_ubfe(w, F.sshift, F.swidth) + F.s_add; /* width 0 extracts 0 */
     } else {
         d = w & 0x7fffffffu;
@@ -157,7 +164,7 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
     for (uint32_t r = r0 + lane; r < r1; r += 64) {
         uint32_t d, s;
         bool done;
-        get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F);
+        get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F, sl.tau);
         const int32_t st = (int32_t)(start_offset(r, sl.tau, sc, sps) - t_s); /* in (-tau, 0) */
         const int32_t en = st + (int32_t)d;
         if (en > 0) { /* still running when the slab begins */
@@ -201,7 +208,7 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
         for (uint32_t j = 0; j < cnt; j++) {
             uint32_t d, s;
             bool done;
-            get_entry<PACKED>(buf, n_cap, sl.off + rb + j, d, done, s, s_scalar, F);
+            get_entry<PACKED>(buf, n_cap, sl.off + rb + j, d, done, s, s_scalar, F, sl.tau);
             const uint32_t st = f - t_s; /* in [0, len) */
             if (st != cur && accN) {
                 atomicAdd(&ev[cur], ((unsigned long long)accN << 32) +
@@ -288,7 +295,7 @@ __device__ __forceinline__ void eval_sparse(const Slot &sl, const Sched &sc, boo
     bool done = false;
     const bool act = (uint32_t)lane < sl.n;
     if (act) {
-        get_entry<PACKED>(buf, n_cap, sl.off + (uint32_t)lane, d, done, s, s_scalar, F);
+        get_entry<PACKED>(buf, n_cap, sl.off + (uint32_t)lane, d, done, s, s_scalar, F, sl.tau);
         f = start_offset((uint32_t)lane, sl.tau, sc, sps);
         if (done)
             sumF += f;
@@ -326,7 +333,7 @@ __device__ __forceinline__ void eval_thin(const Slot &sl, const Sched &sc, bool 
         return;
     uint32_t d, s;
     bool done;
-    get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F);
+    get_entry<PACKED>(buf, n_cap, sl.off + r, d, done, s, s_scalar, F, sl.tau);
     const uint32_t f = start_offset(r, sl.tau, sc, sps);
     if (done)
         sumF += f;
@@ -337,7 +344,7 @@ __device__ __forceinline__ void eval_thin(const Slot &sl, const Sched &sc, bool 
     for (uint32_t q = q_lo; q < q_hi; q++) {
         uint32_t dq, sq;
         bool doneq;
-        get_entry<PACKED>(buf, n_cap, sl.off + q, dq, doneq, sq, s_scalar, F);
+        get_entry<PACKED>(buf, n_cap, sl.off + q, dq, doneq, sq, s_scalar, F, sl.tau);
         const uint32_t fq = start_offset(q, sl.tau, sc, sps);
         if (fq <= t && t < fq + dq)
             occ += sq + 1u + (t - fq);

@@ -60,6 +60,19 @@ __device__ __forceinline__ int32_t wave_max_nonneg(int32_t v)
     return __builtin_amdgcn_readlane(v, 63);
 }
 
+/* bitwise or over the lanes, the same value in every lane */
+__device__ __forceinline__ uint32_t wave_or(uint32_t x)
+{
+    int32_t v = (int32_t)x;
+    v |= dpp_take<0x111, 0xf>(0, v);
+    v |= dpp_take<0x112, 0xf>(0, v);
+    v |= dpp_take<0x114, 0xf>(0, v);
+    v |= dpp_take<0x118, 0xf>(0, v);
+    v |= dpp_take<0x142, 0xa>(0, v);
+    v |= dpp_take<0x143, 0xc>(0, v);
+    return (uint32_t)__builtin_amdgcn_readlane(v, 63);
+}
+
 /* sum over the lanes of 63-bit values, in three limbs of 21 bits */
 __device__ __forceinline__ unsigned long long wave_sum_u63(unsigned long long v)
 {
