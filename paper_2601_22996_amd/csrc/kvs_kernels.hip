@@ -763,11 +763,25 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                 my_cur += c;
             }
         }
-        RawJob nxt;
-        nxt.o = nxt.s = nxt.e = 1;
-        if (!COPY && seg_lo + lane < seg_hi)
-            nxt = load_job(J, row + seg_lo + lane, true);
-        for (uint32_t base = seg_lo; base < seg_hi; base += 64) {
+        /* from memory: the loads of kAhead chunks of 64 jobs are issued together, a wavefront has
+         * little else in flight here */
+        constexpr uint32_t kAhead = COPY ? 1u : 4u;
+        for (uint32_t base0 = seg_lo; base0 < seg_hi; base0 += 64u * kAhead) {
+          RawJob ahead[kAhead];
+          if (!COPY) {
+#pragma unroll
+              for (uint32_t u = 0; u < kAhead; u++) {
+                  const uint32_t i = base0 + 64u * u + (uint32_t)lane;
+                  ahead[u].o = ahead[u].s = ahead[u].e = 1;
+                  if (i < seg_hi)
+                      ahead[u] = load_job(J, row + i, true);
+              }
+          }
+#pragma unroll
+          for (uint32_t u = 0; u < kAhead; u++) {
+            const uint32_t base = base0 + 64u * u;
+            if (base >= seg_hi)
+                break; /* the same for all lanes */
             const uint32_t i = base + (uint32_t)lane;
             const bool act = i < seg_hi;
             uint32_t o, s, ga;
@@ -777,10 +791,7 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                 s = per_job_s ? (w >> 16) : J.s_scalar;
                 ga = act ? (uint32_t)ga_lds[i] : 0u;
             } else {
-                const RawJob raw = nxt;
-                if (i + 64 < seg_hi)
-                    nxt = load_job(J, row + i + 64, true);
-                const JobView v = view_job<EXPLICIT>(raw, J, G, lad, mode, true);
+                const JobView v = view_job<EXPLICIT>(ahead[u], J, G, lad, mode, true);
                 o = v.o;
                 s = v.s;
                 ga = v.ga;
@@ -820,6 +831,7 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                 if ((uint32_t)lane == j)
                     my_cur += (uint32_t)__popcll(bal);
             }
+          }
         }
     };
 
@@ -964,30 +976,52 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
     } else if (GATHERS) {
       if (!bad) {
         /* ---- batches of slots: as many as the phase buffer holds, gathered, then evaluated ---- */
-        if (tid == 0) {
-            uint32_t nb = 0, cnt = 0, used = 0, fill = 0;
-            bstart[0] = 0;
-            auto add = [&](int si) {
-                const uint32_t ns = slot[si].n;
-                if (ns == 0 || slot[si].alias != (uint32_t)si)
-                    return;
-                if (fill + ns > n || cnt - bstart[nb] >= 64u) { /* the buffer or the lanes are full */
-                    bstart[++nb] = (uint8_t)cnt;
+        /* The slots in the order they are evaluated: the levels above the smallest shift, then
+         * the merged first phases.  They are packed into batches one after the other (a batch is
+         * closed when the next slot would overflow the phase buffer or the 64 lanes that keep
+         * track of its slots).  The first wavefront fetches all the sizes at once and then goes
+         * through them in scalar registers: one thread walking the table in LDS would make
+         * every other wavefront wait for some hundred dependent reads. */
+        if (wave == 0) {
+            const uint32_t nlev = (uint32_t)kLevels - 1u - m_min;
+            const uint32_t ncand = nlev + (uint32_t)G.n_m; /* at most kSlots <= 128 */
+            static_assert(kSlots <= 128, "two candidates per lane");
+            auto slot_of = [&](uint32_t k) { return k < nlev ? m_min + 1u + k : (uint32_t)kLevels + (k - nlev); };
+            uint32_t size[2] = {0u, 0u};
+#pragma unroll
+            for (uint32_t h = 0; h < 2u; h++) {
+                const uint32_t k = 64u * h + (uint32_t)lane;
+                if (k < ncand) {
+                    const uint32_t si = slot_of(k);
+                    size[h] = (slot[si].alias == si) ? slot[si].n : 0u;
+                }
+            }
+            uint32_t nb = 0, cnt = 0, first = 0, fill = 0;
+            for (uint32_t k = 0; k < ncand; k++) {
+                const uint32_t ns = (k < 64u) ? __builtin_amdgcn_readlane(size[0], (int)k)
+                                              : __builtin_amdgcn_readlane(size[1], (int)(k - 64u));
+                if (ns == 0)
+                    continue;
+                if (fill + ns > n || cnt - first >= 64u) {
+                    nb++;
+                    if (lane == 0)
+                        bstart[nb] = (uint8_t)cnt;
+                    first = cnt;
                     fill = 0;
                 }
-                slot[si].off = fill;
+                if (lane == 0) {
+                    slot[slot_of(k)].off = fill;
+                    order[cnt] = (uint8_t)slot_of(k);
+                }
                 fill += ns;
-                order[cnt++] = (uint8_t)si;
-                used = 1;
-            };
-            if (mode != MODE_SINGLE)
-                for (int si = (int)m_min + 1; si < kLevels; si++)
-                    add(si);
-            for (int mi = 0; mi < (int)G.n_m; mi++)
-                add(kLevels + mi);
-            if (used)
-                bstart[++nb] = (uint8_t)cnt;
-            n_batches = nb;
+                cnt++;
+            }
+            if (lane == 0) {
+                bstart[0] = 0;
+                if (cnt > 0)
+                    bstart[++nb] = (uint8_t)cnt;
+                n_batches = nb;
+            }
         }
         __syncthreads();
         const uint32_t nb = n_batches;
