@@ -189,6 +189,23 @@ int32_t kvs_paper_ladder(int64_t M, int64_t s, int32_t alpha_num, int32_t alpha_
                          int32_t *ladder, int32_t *n_levels);
 
 /*
+ * The same ladder for a scaling factor that is a quadratic irrational,
+ *   alpha = (a + b sqrt(c)) / d > 1,   a, b, c >= 0, d >= 1
+ * (the factor that minimises the competitive ratio of Algorithm 1 in Theorem
+ * "Competitive Ratio Guarantee of GSA" is (7 + sqrt(13)) / 6).  The powers of
+ * alpha are carried as intervals of 64-bit-mantissa floating-point numbers
+ * that contain the true values; a level or a floor on which the whole interval
+ * agrees is accepted, any other is decided in exact 128-bit integer arithmetic
+ * on alpha^q = (A + B sqrt(c)) / d^q.  Host only.  KVS_EINVAL as above, also
+ * for alpha <= 1; KVS_ELIMIT if more than KVS_MAX_LEVELS levels are needed, or
+ * if some floor(beta alpha^p) lies within about 2^-24 of an integer while the
+ * exact integers no longer fit 128 bits: the call then fails rather than
+ * guess.  The result, when there is one, is exact.
+ */
+int32_t kvs_paper_ladder_quadratic(int64_t M, int64_t s, int32_t a, int32_t b, int32_t c, int32_t d,
+                                   int32_t *ladder, int32_t *n_levels);
+
+/*
  * Scans the job arrays on the device, waits for the result and returns
  * KVS_OK, KVS_EINVAL (some o < 1, s < 0 or o_est < 1), KVS_ERANGE (a length
  * above 2^30) or KVS_EJOB_INFEASIBLE (some s + o > M, Section 2.1).  Optional:

@@ -180,6 +180,50 @@ def paper_ladder(M: int, s: int, num: int, den: int = 1, max_levels: int = 128):
     return lad[:L].copy()
 
 
+def paper_ladder_quadratic(M: int, s: int, a: int, b: int, c: int, d: int):
+    """Slices floor(beta alpha^p), p = 0..l, of Algorithms 1 and 2 for the scaling factor
+    alpha = (a + b sqrt(c)) / d > 1 with integers a, b, c >= 0, d >= 1, in exact integer arithmetic.
+
+    alpha^q = (A + B sqrt(c)) / d^q with integers A, B >= 0, so for integers X, y >= 0
+        y alpha^q <= X  <=>  y B sqrt(c) <= X d^q - y A  <=>  X d^q - y A >= 0 and (y B)^2 c <= (X d^q - y A)^2.
+    l is the largest q with alpha^q <= M - s, and tau_p is the largest y with y alpha^(l-p) <= M - s,
+    found by bisection over y (Python integers do not overflow)."""
+    X = M - s
+    if X < 1 or s < 0 or min(a, b, c) < 0 or d < 1:
+        raise OracleError(EINVAL)
+
+    def times_alpha(A, B):          # (A + B sqrt c)(a + b sqrt c) = (A a + B b c) + (A b + B a) sqrt c
+        return A * a + B * b * c, A * b + B * a
+
+    def le(y, A, B, q):             # y * alpha^q <= X ?
+        rhs = X * d ** q - y * A
+        return rhs >= 0 and (y * B) ** 2 * c <= rhs * rhs
+
+    # alpha > 1  <=>  a + b sqrt(c) > d
+    if not (a > d or (b > 0 and (d - a) ** 2 < b * b * c)):
+        raise OracleError(EINVAL)
+    powers = [(1, 0)]               # alpha^q as (A, B), over d^q
+    while True:
+        A, B = times_alpha(*powers[-1])
+        if not le(1, A, B, len(powers)):
+            break
+        powers.append((A, B))
+    l = len(powers) - 1
+    lad = []
+    for p in range(l + 1):
+        q = l - p
+        A, B = powers[q]
+        lo, hi = 0, X               # largest y in [0, X] with y alpha^q <= X
+        while lo < hi:
+            mid = (lo + hi + 1) // 2
+            if le(mid, A, B, q):
+                lo = mid
+            else:
+                hi = mid - 1
+        lad.append(lo)
+    return np.asarray(lad, np.int32)
+
+
 def ladder_simulate(o, s, M, ladder, sched=SPS, k=0, mode=MODE_GBA, o_est=None):
     """One instance on an explicit ladder of slices.  `s`: int or array."""
     o = _i32(o)

@@ -33,6 +33,7 @@
  */
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <math.h>
 #include <string.h>
 
 #include <atomic>
@@ -1668,6 +1669,98 @@ int32_t kvs_paper_ladder(int64_t M, int64_t s, int32_t alpha_num, int32_t alpha_
         ladder[p] = (int32_t)((span * ad) / an);
         an *= (u128)alpha_num;
         ad *= (u128)alpha_den;
+    }
+    *n_levels = l + 1;
+    return KVS_OK;
+}
+
+int32_t kvs_paper_ladder_quadratic(int64_t M, int64_t s, int32_t a, int32_t b, int32_t c, int32_t d,
+                                   int32_t *ladder, int32_t *n_levels)
+{
+    if (!ladder || !n_levels || s < 0 || M <= s || M - s > (int64_t)kLenMax || a < 0 || b < 0 || c < 0 ||
+        d < 1)
+        return KVS_EINVAL;
+    typedef unsigned __int128 u128;
+    /* alpha and its powers as intervals [lo, hi] of extended-precision numbers that contain the
+     * true values: every operation below is correctly rounded to 64 bits (relative error at most
+     * 2^-64), and widening its result by 2^-62 on either side covers that and leaves room for the
+     * error of the operands' own widening to compound over at most 64 levels. */
+    const long double eps = 0x1p-62L;
+    const long double root = sqrtl((long double)c);
+    const long double alpha = ((long double)a + (long double)b * root) / (long double)d;
+    const long double a_lo = alpha * (1.0L - eps), a_hi = alpha * (1.0L + eps);
+    if (!(a_lo > 1.0L))
+        return KVS_EINVAL; /* alpha <= 1, or too close to 1 to tell */
+    const u128 X = (u128)(M - s);
+    const long double span = (long double)(M - s);
+    /* Beside the intervals, alpha^q = (A_q + B_q sqrt(c)) / d^q in integers while they fit 128
+     * bits: where an interval cannot decide a comparison (powers of sqrt(2) hit integers), it is
+     * decided exactly:  y alpha^q <= X  <=>  X d^q - y A_q >= 0 and (y B_q)^2 c <= (X d^q - y A_q)^2. */
+    u128 eA[KVS_MAX_LEVELS + 2], eB[KVS_MAX_LEVELS + 2], eD[KVS_MAX_LEVELS + 2];
+    bool exact[KVS_MAX_LEVELS + 2];
+    eA[0] = 1; eB[0] = 0; eD[0] = 1; exact[0] = true;
+    auto mul = [](u128 x, u128 y, u128 &r) { return !__builtin_mul_overflow(x, y, &r); };
+    auto next_exact = [&](int q) { /* level q + 1 from level q */
+        u128 t1, t2, t3, t4, t5, nd;
+        exact[q + 1] = exact[q] && mul(eA[q], (u128)a, t1) && mul(eB[q], (u128)b, t2) && mul(t2, (u128)c, t3) &&
+                       mul(eA[q], (u128)b, t4) && mul(eB[q], (u128)a, t5) && mul(eD[q], (u128)d, nd) &&
+                       !__builtin_add_overflow(t1, t3, &eA[q + 1]) && !__builtin_add_overflow(t4, t5, &eB[q + 1]);
+        if (exact[q + 1])
+            eD[q + 1] = nd;
+    };
+    /* 1: y alpha^q <= X, 0: not, -1: does not fit 128 bits */
+    auto exact_le = [&](u128 y, int q) -> int {
+        u128 xd, ya, yb, lhs, rhs;
+        if (!exact[q] || !mul(X, eD[q], xd) || !mul(y, eA[q], ya) || !mul(y, eB[q], yb))
+            return -1;
+        if (xd < ya)
+            return 0;
+        const u128 r = xd - ya;
+        if (!mul(yb, yb, lhs) || !mul(lhs, (u128)c, lhs) || !mul(r, r, rhs))
+            return -1;
+        return lhs <= rhs ? 1 : 0;
+    };
+    long double pw_lo[KVS_MAX_LEVELS + 2], pw_hi[KVS_MAX_LEVELS + 2]; /* alpha^j */
+    pw_lo[0] = pw_hi[0] = 1.0L;
+    int l = 0; /* the largest j with alpha^j <= M - s */
+    for (;;) {
+        if (l + 1 > KVS_MAX_LEVELS)
+            return KVS_ELIMIT;
+        const long double n_lo = pw_lo[l] * a_lo * (1.0L - eps), n_hi = pw_hi[l] * a_hi * (1.0L + eps);
+        next_exact(l);
+        if (n_lo > span)
+            break; /* alpha^(l+1) > M - s for certain */
+        if (!(n_hi <= span)) { /* too close to M - s for the interval */
+            const int le = exact_le(1, l + 1);
+            if (le < 0)
+                return KVS_ELIMIT;
+            if (le == 0)
+                break;
+        }
+        pw_lo[l + 1] = n_lo;
+        pw_hi[l + 1] = n_hi;
+        l++;
+    }
+    /* tau_p = floor(beta alpha^p) = floor((M - s) / alpha^(l-p)); the top one is M - s itself */
+    for (int p = 0; p <= l; p++) {
+        const int q = l - p;
+        if (q == 0) {
+            ladder[p] = (int32_t)(M - s);
+            continue;
+        }
+        const long double x_lo = span / pw_hi[q] * (1.0L - eps), x_hi = span / pw_lo[q] * (1.0L + eps);
+        const long double f_lo = floorl(x_lo), f_hi = floorl(x_hi);
+        if (f_lo == f_hi) {
+            ladder[p] = (int32_t)f_lo;
+            continue;
+        }
+        /* an integer lies inside the interval: the floor is it, or the one below */
+        if (f_hi != f_lo + 1.0L || f_lo < 0.0L)
+            return KVS_ELIMIT;
+        const int le = exact_le((u128)f_hi, q);
+        if (le < 0)
+            return KVS_ELIMIT;
+        ladder[p] = (int32_t)(le ? f_hi : f_lo);
     }
     *n_levels = l + 1;
     return KVS_OK;

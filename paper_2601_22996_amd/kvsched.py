@@ -64,6 +64,8 @@ def lib():
         L.kvs_ladder_simulate.argtypes = [C.POINTER(_Jobs)] + [C.POINTER(i32)] * 5 + [i32, vp, vp, vp, vp, vp]
         L.kvs_paper_ladder.restype = i32
         L.kvs_paper_ladder.argtypes = [C.c_int64, C.c_int64, i32, i32, C.POINTER(i32), C.POINTER(i32)]
+        L.kvs_paper_ladder_quadratic.restype = i32
+        L.kvs_paper_ladder_quadratic.argtypes = [C.c_int64, C.c_int64, i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
         L.kvs_validate.restype = i32
         L.kvs_validate.argtypes = [C.POINTER(_Jobs), vp]
         L.kvs_validate_static.restype = i32
@@ -169,6 +171,15 @@ def paper_ladder(M: int, s: int, alpha_num: int, alpha_den: int = 1) -> np.ndarr
     n = C.c_int32(0)
     _check(lib().kvs_paper_ladder(int(M), int(s), int(alpha_num), int(alpha_den),
                                   lad.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(n)))
+    return lad[:n.value].copy()
+
+
+def paper_ladder_quadratic(M: int, s: int, a: int, b: int, c: int, d: int) -> np.ndarray:
+    """kvs_paper_ladder_quadratic: the slices for alpha = (a + b sqrt(c)) / d (host only)."""
+    lad = np.zeros(MAX_LEVELS, np.int32)
+    n = C.c_int32(0)
+    _check(lib().kvs_paper_ladder_quadratic(int(M), int(s), int(a), int(b), int(c), int(d),
+                                            lad.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(n)))
     return lad[:n.value].copy()
 
 

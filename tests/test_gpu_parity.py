@@ -172,9 +172,11 @@ def test_explicit_ladders(K, n, I, hetero, est):
     # the paper's ladders for three scaling factors, a ladder with repeated and irregular
     # slices, and one that is the doubling ladder written out
     ladders = [K.paper_ladder(M, smax, 2), K.paper_ladder(M, smax, 3, 2), K.paper_ladder(M, smax, 4, 3),
+               K.paper_ladder_quadratic(M, smax, 7, 1, 13, 6),     # the factor tuned for Algorithm 1
                np.array([1, 1, 3, 3, 3, 10, 11, 50, 200, 200, 1000, 5000], np.int32),
                np.array([2 << p for p in range(12)], np.int32)]
     assert ladders[0].tolist() == O.paper_ladder(M, smax, 2).tolist()
+    assert ladders[3].tolist() == O.paper_ladder_quadratic(M, smax, 7, 1, 13, 6).tolist()
     lads, pts = [], []
     for lad in ladders:
         for sched, k, mode in ((0, 0, 0), (1, 0, 0), (0, 0, 1), (1, 5, 1), (0, 3, 0)):

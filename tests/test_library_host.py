@@ -174,6 +174,43 @@ def test_paper_ladder_matches_the_oracle_and_the_definition(L):
     assert lib_ladder(2 ** 30, 0, 4, 3)[0] == 5                    # needs more than 64 levels
 
 
+def test_quadratic_ladder_matches_the_exact_oracle_or_refuses(L):
+    # the library works with intervals of 64-bit-mantissa numbers and falls back on 128-bit integers:
+    # where it answers, the answer is the exact ladder (the oracle's, in unbounded integer
+    # arithmetic); where neither can decide a floor it says KVS_ELIMIT
+    import numpy as np
+    import oracle as O
+    L.kvs_paper_ladder_quadratic.restype = C.c_int32
+    L.kvs_paper_ladder_quadratic.argtypes = [C.c_int64, C.c_int64] + [C.c_int32] * 4 + [C.POINTER(C.c_int32)] * 2
+
+    def lib(M, s, a, b, c, d):
+        lad, n = (C.c_int32 * 64)(), C.c_int32()
+        rc = L.kvs_paper_ladder_quadratic(M, s, a, b, c, d, lad, C.byref(n))
+        return rc, list(lad[:n.value])
+
+    rng = random.Random(5)
+    answered = 0
+    for a, b, c, d in [(7, 1, 13, 6), (1, 1, 5, 2), (0, 1, 2, 1), (3, 2, 3, 4), (0, 1, 3, 1), (5, 3, 7, 9)]:
+        for _ in range(200):
+            s = rng.randrange(0, 3000)
+            M = s + rng.choice([1, 2, 3, 10, 160, 1000, 4096, 65536, 10 ** 6, 2 ** 30, rng.randrange(1, 2 ** 30)])
+            rc, lad = lib(M, s, a, b, c, d)
+            assert rc in (0, 5), rc
+            if rc == 0:
+                answered += 1
+                assert lad == O.paper_ladder_quadratic(M, s, a, b, c, d).tolist(), (M, s, a, b, c, d)
+    assert answered >= 1190            # undecidable floors are rare
+    assert lib(256, 96, 7, 1, 13, 6) == (0, [1, 2, 5, 9, 16, 28, 51, 90, 160])
+    # floors that are hit exactly (a rational factor, powers of sqrt 2) are decided in integers
+    assert lib(256, 96, 2, 0, 0, 1) == (0, [1, 2, 5, 10, 20, 40, 80, 160])
+    assert lib(1024, 0, 0, 1, 2, 1)[1] == O.paper_ladder_quadratic(1024, 0, 0, 1, 2, 1).tolist()
+    assert lib(100, 0, 1, 0, 0, 1)[0] == 1                                           # alpha = 1
+    assert lib(100, 100, 7, 1, 13, 6)[0] == 1 and lib(2 ** 31, 0, 7, 1, 13, 6)[0] == 1
+    assert lib(2 ** 30, 0, 0, 1, 0, 1000)[0] == 1                                    # alpha = 0
+    # a factor so close to 1 that 64 levels do not reach M - s
+    assert lib(2 ** 20, 0, 100, 1, 2, 101)[0] == 5
+
+
 def test_floor_sum_matches_the_plain_sum(L):
     L.kvs_host_floor_sum.restype = C.c_uint64
     L.kvs_host_floor_sum.argtypes = [C.c_uint64] * 3

@@ -684,3 +684,62 @@ def test_event_evaluator_equals_the_stepper_on_the_workloads(cfg):
         assert np.array_equal(a[key], b[key]), key
     with pytest.raises(O.OracleError):
         O.gba_simulate_batch(np.array([[5, 500]], np.int32), 10, 100, [(1, 0, 0, 0)], evaluator="events")
+
+
+# --------------------------------------------------------------------------
+# The ladder for an irrational scaling factor: alpha = (7 + sqrt 13) / 6 is the
+# factor Theorem "Competitive Ratio Guarantee of GSA" tunes for general instances
+# --------------------------------------------------------------------------
+def test_quadratic_ladder_against_high_precision_arithmetic():
+    # independent of the oracle's integer comparisons: 120-digit decimal arithmetic, whose error
+    # (about 1e-115) is far below the distance of any beta alpha^p from an integer that could
+    # occur here (the values are algebraic of degree 2 with small coefficients)
+    from decimal import Decimal, getcontext
+    getcontext().prec = 120
+    rng = np.random.default_rng(8)
+    for a, b, c, d in [(7, 1, 13, 6), (1, 1, 5, 2), (0, 1, 2, 1), (3, 2, 3, 4), (1, 1, 2, 2)]:
+        alpha = (Decimal(a) + Decimal(b) * Decimal(c).sqrt()) / Decimal(d)
+        assert alpha > 1
+        for _ in range(30):
+            s = int(rng.integers(0, 500))
+            M = s + int(rng.choice([1, 2, 7, 160, 4096, 99991, 2 ** 30]))
+            lad = O.paper_ladder_quadratic(M, s, a, b, c, d)
+            l = len(lad) - 1
+            assert alpha ** l <= M - s < alpha ** (l + 1)
+            beta = Decimal(M - s) / alpha ** l
+            assert 1 <= beta < alpha
+            for p in range(l + 1):
+                assert int(lad[p]) == int((beta * alpha ** p).to_integral_value(rounding="ROUND_FLOOR")), (a, b, c, d, M, s, p)
+            assert lad[-1] == M - s and (np.diff(lad) >= 0).all()
+    # a rational factor written as a quadratic one gives the rational ladder
+    assert O.paper_ladder_quadratic(256, 96, 2, 0, 0, 1).tolist() == GOLD["two_point_gsa"]["ladder"] \
+        if "ladder" in GOLD.get("two_point_gsa", {}) else True
+    assert O.paper_ladder_quadratic(1000, 7, 3, 0, 5, 2).tolist() == O.paper_ladder(1000, 7, 3, 2).tolist()
+    assert O.paper_ladder_quadratic(1000, 7, 1, 1, 4, 2).tolist() == O.paper_ladder(1000, 7, 3, 2).tolist()
+    with pytest.raises(O.OracleError):
+        O.paper_ladder_quadratic(100, 0, 1, 0, 0, 1)      # alpha = 1
+
+
+def test_gsa_ratio_theorem_at_the_tuned_irrational_factor():
+    # Theorem "Competitive Ratio Guarantee of GSA": with alpha = (7 + sqrt 13) / 6 and k_min >= 1 the
+    # flow time of Algorithm 1 is at most (92 + 26 sqrt 13) / 3 = 61.9147... times the optimum.
+    # (92 + 26 sqrt 13) / 3 >= 61.9147, so flow * 10000 <= 619147 * OPT is implied by the theorem.
+    import math
+    assert 92 + 26 * math.sqrt(13) > 3 * 61.9147
+    alpha = (7 + math.sqrt(13)) / 6
+    gamma = (2 + 2 / (alpha - 1)) * (3 * alpha ** 2 + alpha + alpha / (alpha - 1))
+    assert abs(gamma - (92 + 26 * math.sqrt(13)) / 3) < 1e-9     # the closed form of the minimum
+    rng = np.random.default_rng(13)
+    worst = 0.0
+    for _ in range(40):
+        s = int(rng.integers(0, 5))
+        M = s + int(rng.integers(8, 40))
+        n = int(rng.integers(1, 6))
+        o = rng.integers(1, min(8, M - s) + 1, n).astype(np.int32)
+        lad = O.paper_ladder_quadratic(M, s, 7, 1, 13, 6)
+        opt = O.opt_exact(o, s, M)
+        gsa = O.ladder_simulate(o, s, M, lad, mode=O.MODE_GSA)
+        assert gsa["feasible"] == 1
+        assert gsa["flow"] * 10000 <= 619147 * opt
+        worst = max(worst, gsa["flow"] / opt)
+    assert worst >= 1.0
