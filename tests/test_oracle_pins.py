@@ -709,11 +709,15 @@ def test_quadratic_ladder_against_high_precision_arithmetic():
             beta = Decimal(M - s) / alpha ** l
             assert 1 <= beta < alpha
             for p in range(l + 1):
-                assert int(lad[p]) == int((beta * alpha ** p).to_integral_value(rounding="ROUND_FLOOR")), (a, b, c, d, M, s, p)
+                x = beta * alpha ** p
+                near = x.to_integral_value(rounding="ROUND_HALF_EVEN")
+                # a value that IS an integer (the top slice M - s; even powers of sqrt 2) comes out of
+                # the decimal arithmetic a hair beside it
+                want = near if abs(x - near) < Decimal(10) ** -100 else x.to_integral_value(rounding="ROUND_FLOOR")
+                assert int(lad[p]) == int(want), (a, b, c, d, M, s, p)
             assert lad[-1] == M - s and (np.diff(lad) >= 0).all()
     # a rational factor written as a quadratic one gives the rational ladder
-    assert O.paper_ladder_quadratic(256, 96, 2, 0, 0, 1).tolist() == GOLD["two_point_gsa"]["ladder"] \
-        if "ladder" in GOLD.get("two_point_gsa", {}) else True
+    assert O.paper_ladder_quadratic(256, 96, 2, 0, 0, 1).tolist() == [1, 2, 5, 10, 20, 40, 80, 160]
     assert O.paper_ladder_quadratic(1000, 7, 3, 0, 5, 2).tolist() == O.paper_ladder(1000, 7, 3, 2).tolist()
     assert O.paper_ladder_quadratic(1000, 7, 1, 1, 4, 2).tolist() == O.paper_ladder(1000, 7, 3, 2).tolist()
     with pytest.raises(O.OracleError):
