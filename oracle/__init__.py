@@ -94,6 +94,11 @@ def lib():
         _lib.kvo_area_lb.argtypes = [i64, p32, p32, i64, p64]
         _lib.kvo_upper_gba.restype = C.c_int
         _lib.kvo_upper_gba.argtypes = [i64, p32, p32, i64, i64, i64, p64]
+        _lib.kvo_gbad_simulate.restype = C.c_int
+        _lib.kvo_gbad_simulate.argtypes = [i64, p32, p32, i64, i64, i64, C.c_int, i64, p64, p32, p64, p64, p64, p64]
+        _lib.kvo_gbad_simulate_batch.restype = C.c_int
+        _lib.kvo_gbad_simulate_batch.argtypes = [i64, i64, i64, p32, p32, i64, i64, i64, p32, p32, p32,
+                                                 p64, pu8, p64, p64]
         _lib.kve_gba_simulate_batch.restype = C.c_int
         _lib.kve_gba_simulate_batch.argtypes = _lib.kvo_gba_simulate_batch.argtypes
         _lib.kve_ladder_simulate.restype = C.c_int
@@ -350,6 +355,62 @@ def schedule_eval_batch(o, s, M, points, i0=0, i1=None):
                                          feas.ctypes.data_as(C.POINTER(C.c_uint8)), _p64(flow),
                                          _p32(nc), _p64(steps)))
     return dict(peak=peak, feasible=feas, flow=flow, n_completed=nc, job_steps=steps)
+
+
+def gbad_simulate(o, s, M, tau0=1, sched=SPS, k=0, starts=False):
+    """Algorithm 2 with dynamic refill (GBA-D) on one instance.  `starts`: also return the start
+    round of every job in the refilled and in the baseline schedule."""
+    o = _i32(o)
+    s_arr = None if np.isscalar(s) else _i32(s)
+    s_scalar = int(s) if np.isscalar(s) else 0
+    peak, flow, steps = C.c_int64(), C.c_int64(), C.c_int64()
+    feas = C.c_int32()
+    st = np.zeros(len(o), np.int64)
+    bs = np.zeros(len(o), np.int64)
+    _check(lib().kvo_gbad_simulate(len(o), _p32(o), _p32(s_arr), s_scalar, M, tau0, sched, k,
+                                   C.byref(peak), C.byref(feas), C.byref(flow), C.byref(steps),
+                                   _p64(st), _p64(bs)))
+    r = dict(peak=peak.value, feasible=feas.value, flow=flow.value, job_steps=steps.value)
+    if starts:
+        r["start"], r["base_start"] = st, bs
+    return r
+
+
+def gbad_simulate_batch(o, s, M, points, i0=0, i1=None, threads=1):
+    """GBA-D on instances [i0, i1) at every point (tau0, sched, k); arrays [n_pts][i1 - i0]."""
+    o = _i32(o)
+    I, n = o.shape
+    i1 = I if i1 is None else i1
+    s_arr = None if np.isscalar(s) else _i32(s)
+    s_scalar = int(s) if np.isscalar(s) else 0
+    pts = np.asarray(points, dtype=np.int32).reshape(-1, 3)
+    tau0, sched, k = (np.ascontiguousarray(pts[:, j]) for j in range(3))
+    P = len(pts)
+    pu8 = C.POINTER(C.c_uint8)
+
+    def run(a, b):
+        part = dict(peak=np.zeros((P, b - a), np.int64), feasible=np.zeros((P, b - a), np.uint8),
+                    flow=np.zeros((P, b - a), np.int64), job_steps=np.zeros((P, b - a), np.int64))
+        rc = lib().kvo_gbad_simulate_batch(a, b, n, _p32(o), _p32(s_arr), s_scalar, M, P, _p32(tau0),
+                                           _p32(sched), _p32(k), _p64(part["peak"]),
+                                           part["feasible"].ctypes.data_as(pu8), _p64(part["flow"]),
+                                           _p64(part["job_steps"]))
+        return rc, part
+
+    threads = max(1, min(int(threads), i1 - i0))
+    if threads == 1:
+        rc, out = run(i0, i1)
+        _check(rc)
+        return out
+    from concurrent.futures import ThreadPoolExecutor
+    cuts = np.linspace(i0, i1, 4 * threads + 1).astype(np.int64)
+    spans = [(int(a), int(b)) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+    with ThreadPoolExecutor(threads) as ex:
+        parts = list(ex.map(lambda ab: run(*ab), spans))
+    for rc, _ in parts:
+        _check(rc)
+    return {key: np.concatenate([part[key] for _, part in parts], axis=1)
+            for key in ("peak", "feasible", "flow", "job_steps")}
 
 
 def opt_perm(o, s: int, M: int) -> int:

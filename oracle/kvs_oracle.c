@@ -20,6 +20,8 @@
  *   - Geometric-Slicing-Algorithm (GSA): Algorithm 1;
  *   - Geometric-Batching-Algorithm (GBA): Algorithm 2;
  *   - memory-time area: Definition "Memory-Time Area";
+ *   - dynamic refill (GBA-D): appendix "Numerical Experiments", paragraph
+ *     "Dynamic Refill";
  *   - OPT: Section 2.1 ("Objective and Benchmark") and its footnote that
  *     neither preemption nor pausing is needed in an optimal schedule.
  *
@@ -42,7 +44,12 @@
  * search.  The ladder of Algorithms 1 and 2: exact rational arithmetic.  The
  * bounds (kvo_upper_gba, kvo_area_lb): printed values, hand examples, the
  * lemmas as inequalities against the stepped flow and the exhaustive optimum.
- * Parity unpinned by anything the paper prints: the treatment of estimates
+ * Algorithm 2 with dynamic refill (kvo_gbad_simulate): hand-worked cases, a
+ * second implementation, the paper's claims about it (no job later than in
+ * Algorithm 2's schedule, within the budget) and the toy example, where
+ * nothing can move (180).
+ * Parity unpinned by anything the paper prints: the refill rule itself (one
+ * sentence in the appendix; the reading is stated at the function); the treatment of estimates
  * other than the two ends (estimate = true length, estimate = 1) to which it
  * reduces; per-job prompt lengths (only the invariant MemPeak <= M); the
  * order of the jobs inside a phase; a job shorter than its slice leaving the
@@ -834,5 +841,159 @@ int kvo_upper_gba(int64_t n, const int32_t *o, const int32_t *s, int64_t s_scala
         total += cnt[p] * S + Q;
     }
     *upper = total;
+    return KVO_OK;
+}
+
+/* ------------------------------------------------------------------------ */
+/* GBA with dynamic refill ("GBA-D", appendix "Numerical Experiments")        */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * The appendix describes the variant in one sentence: a job is admitted as
+ * soon as the pipeline can go on with it without violating memory
+ * feasibility, and no job is ever delayed relative to the schedule of
+ * Algorithm 2, whose idle time it only fills.  The reading taken here (the
+ * paper prints no value that would pin another):
+ *
+ *   - the baseline is the schedule of Algorithm 2 on the ladder tau_0 * 2^p
+ *     (subroutine, parallelism as for kvo_gba_simulate, true lengths as
+ *     classes); every job first holds its baseline slot with its actual run
+ *     (o_i rounds from its baseline start);
+ *   - the jobs are taken in the baseline's order (class by class, input order
+ *     inside a class).  Each is moved to the earliest round, not before the
+ *     start of the job before it in that order and not after its own baseline
+ *     start, at which its whole run fits in every round on top of the runs of
+ *     all the other jobs where they stand now: the earlier ones where they were
+ *     moved to, the later ones still at their baseline starts.
+ *
+ * Because the later jobs keep their places in the test, every job can always
+ * fall back on its baseline start: no job is delayed, and the schedule stays
+ * within the budget whenever the baseline does.  (Testing against the earlier
+ * jobs alone would not do: a job moved up is further along, hence larger,
+ * when a later one wants its baseline slot.)
+ *
+ * start_out / base_start_out (may be NULL): start round of every job in the
+ * refilled and in the baseline schedule.
+ */
+int kvo_gbad_simulate(int64_t n, const int32_t *o, const int32_t *s,
+                      int64_t s_scalar, int64_t M, int64_t tau0, int sched,
+                      int64_t k, int64_t *peak, int32_t *feasible,
+                      int64_t *flow, int64_t *job_steps, int64_t *start_out,
+                      int64_t *base_start_out)
+{
+    int64_t *cls = NULL, *order = NULL, *base = NULL, *start = NULL, *occ = NULL;
+    int64_t i, j, p, maxcls = 0, pos = 0, begin = 0, horizon, prev = 0, pk = 0, fl = 0, steps = 0;
+    int rc = KVO_OK;
+
+    if (n < 0 || M <= 0 || tau0 < 1 || k < 0 || (sched != KVO_SPS && sched != KVO_SIMS))
+        return KVO_EINVAL;
+    for (i = 0; i < n; i++) {
+        int64_t si = s ? s[i] : s_scalar;
+        if (o[i] < 1 || si < 0)
+            return KVO_EINVAL;
+        if (si + o[i] > M)
+            return KVO_EJOB_INFEASIBLE;
+    }
+    cls = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    order = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    base = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    start = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    if (!cls || !order || !base || !start) {
+        rc = KVO_ENOMEM;
+        goto out;
+    }
+    /* classes of Algorithm 2: the first slice tau_0 * 2^p that covers the length */
+    for (i = 0; i < n; i++) {
+        int64_t t = tau0;
+        for (p = 0; t < o[i]; p++)
+            t *= 2;
+        cls[i] = p;
+        if (p > maxcls)
+            maxcls = p;
+    }
+    /* the baseline: class after class, Procedure 1 (or the simultaneous schedule) inside */
+    for (p = 0; p <= maxcls; p++) {
+        int64_t tau = tau0 << p, n_p = 0, s_max = 0, kk, r = 0;
+        for (i = 0; i < n; i++)
+            if (cls[i] == p) {
+                int64_t si = s ? s[i] : s_scalar;
+                n_p++;
+                if (si > s_max)
+                    s_max = si;
+            }
+        if (n_p == 0)
+            continue;
+        kk = phase_parallelism(sched, tau, s_max, M, k);
+        for (i = 0; i < n; i++)
+            if (cls[i] == p) {
+                base[i] = begin + start_offset(sched, r, tau, kk);
+                order[pos++] = i;
+                r++;
+            }
+        begin += start_offset(sched, n_p - 1, tau, kk) + tau;
+    }
+    horizon = begin + 1;
+    occ = (int64_t *)calloc((size_t)horizon, sizeof(int64_t));
+    if (!occ) {
+        rc = KVO_ENOMEM;
+        goto out;
+    }
+    for (i = 0; i < n; i++) {
+        start[i] = base[i];
+        place(occ, base[i], o[i], s ? s[i] : s_scalar, +1);
+    }
+    /* refill: one job after the other, in the baseline's order */
+    for (j = 0; j < n; j++) {
+        int64_t t, si;
+        i = order[j];
+        si = s ? s[i] : s_scalar;
+        place(occ, base[i], o[i], si, -1);
+        for (t = prev; t < base[i]; t++)
+            if (fits(occ, horizon, t, o[i], si, M))
+                break;
+        start[i] = t; /* its baseline start if nothing earlier fits */
+        place(occ, t, o[i], si, +1);
+        prev = t;
+    }
+    for (i = 0; i < horizon; i++)
+        if (occ[i] > pk)
+            pk = occ[i];
+    for (i = 0; i < n; i++) {
+        fl += start[i] + o[i];
+        steps += o[i];
+        if (start_out)
+            start_out[i] = start[i];
+        if (base_start_out)
+            base_start_out[i] = base[i];
+    }
+    *peak = pk;
+    *feasible = pk <= M ? 1 : 0;
+    *flow = fl;
+    *job_steps = steps;
+out:
+    free(cls); free(order); free(base); free(start); free(occ);
+    return rc;
+}
+
+/* Instances [i0, i1) at every point (tau0, sched, k); outputs [n_pts][i1 - i0]. */
+int kvo_gbad_simulate_batch(int64_t i0, int64_t i1, int64_t n, const int32_t *o,
+                            const int32_t *s, int64_t s_scalar, int64_t M,
+                            int64_t n_pts, const int32_t *tau0,
+                            const int32_t *sched, const int32_t *k,
+                            int64_t *peak, uint8_t *feasible, int64_t *flow,
+                            int64_t *job_steps)
+{
+    int64_t q, i, cnt = i1 - i0;
+    for (q = 0; q < n_pts; q++)
+        for (i = i0; i < i1; i++) {
+            int32_t feas = 0;
+            int64_t idx = q * cnt + (i - i0);
+            int rc = kvo_gbad_simulate(n, o + i * n, s ? s + i * n : NULL, s_scalar, M, tau0[q],
+                                       sched[q], k[q], &peak[idx], &feas, &flow[idx],
+                                       &job_steps[idx], NULL, NULL);
+            if (rc != KVO_OK)
+                return rc;
+            feasible[idx] = (uint8_t)feas;
+        }
     return KVO_OK;
 }

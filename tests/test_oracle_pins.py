@@ -747,3 +747,143 @@ def test_gsa_ratio_theorem_at_the_tuned_irrational_factor():
         assert gsa["flow"] * 10000 <= 619147 * opt
         worst = max(worst, gsa["flow"] / opt)
     assert worst >= 1.0
+
+
+# --------------------------------------------------------------------------
+# Algorithm 2 with dynamic refill (GBA-D, appendix "Numerical Experiments").
+# The paper gives the rule in a sentence and prints no value for it: these pins
+# are hand-worked cases of the reading stated in the oracle, a second
+# implementation of that reading, and the properties the paper claims for it.
+# --------------------------------------------------------------------------
+def py_gbad(o, s, M, tau0):
+    """Second implementation (SPS, automatic parallelism): occupancy as plain per-round lists."""
+    n = len(o)
+    s_arr = [s] * n if np.isscalar(s) else list(s)
+    cls = []
+    for x in o:
+        p = 0
+        while tau0 * (1 << p) < x:
+            p += 1
+        cls.append(p)
+    order = sorted(range(n), key=lambda i: (cls[i], i))
+    base, begin = [0] * n, 0
+    for p in sorted(set(cls)):
+        part = [i for i in order if cls[i] == p]
+        tau = tau0 << p
+        smax = max(s_arr[i] for i in part)
+        k = 0
+        while py_gcd_peak(k + 1, tau, smax) <= M:
+            k += 1
+        k = max(k, 1)
+        for r, i in enumerate(part):
+            base[i] = begin + r * tau // k
+        begin += (len(part) - 1) * tau // k + tau
+
+    def usage(starts):
+        occ = [0] * (begin + 1)
+        for i in range(n):
+            for u in range(o[i]):
+                occ[starts[i] + u] += s_arr[i] + u + 1
+        return occ
+
+    start, prev = list(base), 0
+    for i in order:
+        for t in range(prev, base[i]):
+            trial = list(start)
+            trial[i] = t
+            if max(usage(trial)) <= M:
+                start[i] = t
+                break
+        prev = start[i]
+    return dict(start=start, base=base, flow=sum(start[i] + o[i] for i in range(n)), peak=max(usage(start)) if n else 0)
+
+
+def test_gbad_hand_worked_cases():
+    # Three jobs of length 2, s = 0, M = 4, slice 2: Peak(2, 2, 0) = 3 <= 4 < Peak(3, 2, 0) = 5, so the
+    # baseline starts them at 0, 1, 2 (flow 2 + 3 + 4).  Job 1 may move to round 0: rounds 0, 1 then hold
+    # 1 + 1 and 2 + 2, and job 2 still fits at 2.  Job 2 cannot move: at 0 or 1 round 1 would hold
+    # 2 + 2 + (2 or 1) > 4.  Flow 2 + 2 + 4.
+    r = O.gbad_simulate([2, 2, 2], 0, 4, tau0=2, starts=True)
+    assert r["base_start"].tolist() == [0, 1, 2] and r["start"].tolist() == [0, 0, 2]
+    assert (r["flow"], r["peak"], r["feasible"], r["job_steps"]) == (8, 4, 1, 6)
+    # Plenty of memory: s = 1, M = 10, slice 4, lengths 1, 4, 3, 2; k*(4, 1, 10) = 2 (Peak = 8, then 12), the
+    # baseline starts at 0, 2, 4, 6 and leaves the slices mostly idle (flow 1 + 6 + 7 + 8).  Refilled,
+    # everybody starts at 0: round 0 holds 4 x 2 = 8, round 1 holds 3 x 3 = 9, round 2 holds 2 x 4, round 3
+    # holds 5.  Flow 1 + 4 + 3 + 2.
+    r = O.gbad_simulate([1, 4, 3, 2], 1, 10, tau0=4, starts=True)
+    assert r["base_start"].tolist() == [0, 2, 4, 6] and r["start"].tolist() == [0, 0, 0, 0]
+    assert (r["flow"], r["peak"], r["feasible"]) == (10, 9, 1)
+    assert O.gba_simulate([1, 4, 3, 2], 1, 10, tau0=4)["flow"] == 22
+    # Why the later jobs keep their slots in the test.  Three jobs of length 4, s = 0, M = 9, slice 4,
+    # k*(4, 0, 9) = 3 (Peak = 9): baseline starts 0, 1, 2 and round 3 holds 4 + 3 + 2 = 9 = M.  Job 1 alone
+    # would fit at round 0 on top of job 0 (round 3: 4 + 4 = 8), but job 2 at its slot would then see
+    # 4 + 4 + 2 = 10 in round 3 and would have to wait until round 3, later than in the baseline.  So job 1
+    # stays at 1 and the schedule is the baseline's.
+    r = O.gbad_simulate([4, 4, 4], 0, 9, tau0=1, starts=True)
+    assert r["base_start"].tolist() == [0, 1, 2] and r["start"].tolist() == [0, 1, 2]
+    assert (r["flow"], r["peak"]) == (15, 9)
+    # Example 1 of the paper: every slice is full and the pipeline runs at M, nothing can move: 180.
+    g = GOLD["example1_sps"]
+    r = O.gbad_simulate([g["o"]] * g["n"], g["s"], g["M"], tau0=g["o"], starts=True)
+    assert r["flow"] == g["flow"] == 180 and r["start"].tolist() == list(range(15))
+    # the uniform experiment has two units of slack under M = 256 (Peak = 254): a few jobs move up
+    u = GOLD["uniform_gba"]
+    assert O.gbad_simulate([u["o"]] * u["n"], u["s"], u["M"], tau0=1)["flow"] <= u["flow"] == 14083
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_gbad_properties_and_second_implementation(seed):
+    rng = np.random.default_rng(4000 + seed)
+    moved = 0
+    for it in range(120):
+        n = int(rng.integers(1, 28))
+        omax = int(rng.choice([3, 9, 40]))
+        o = rng.integers(1, omax + 1, n).astype(np.int32)
+        hetero = bool(rng.integers(0, 2))
+        s = rng.integers(0, 12, n).astype(np.int32) if hetero else int(rng.integers(0, 12))
+        M = int(np.max(s) + omax + rng.choice([0, 2, 15, 120]))
+        tau0 = int(rng.choice([1, 2, 3, 5]))
+        r = O.gbad_simulate(o, s, M, tau0=tau0, starts=True)
+        g = O.gba_simulate(o, s, M, tau0)
+        # what the paper claims: no job later than in Algorithm 2's schedule, and within the budget
+        assert (r["start"] <= r["base_start"]).all()
+        assert r["flow"] <= g["flow"] and r["peak"] <= M and r["feasible"] == 1
+        assert r["flow"] >= int(o.sum()) and r["job_steps"] == g["job_steps"] == int(o.sum())
+        assert int((r["base_start"] + o).sum()) == g["flow"]          # the baseline is Algorithm 2's schedule
+        # the refilled schedule stepped as explicit runs gives the same peak
+        idx = np.argsort(r["start"], kind="stable")
+        s_arr = np.full(n, s) if np.isscalar(s) else s
+        assert O.step_runs(r["start"][idx], o[idx], s_arr[idx])[0] == r["peak"]
+        moved += int((r["start"] < r["base_start"]).sum())
+        if it % 4 == 0:                                               # the slow second implementation
+            p = py_gbad(o.tolist(), s if np.isscalar(s) else s.tolist(), M, tau0)
+            assert p["start"] == r["start"].tolist() and p["base"] == r["base_start"].tolist()
+            assert p["flow"] == r["flow"] and p["peak"] == r["peak"]
+        if n <= 5 and omax <= 9 and not hetero:
+            assert r["flow"] >= O.opt_exact(o, s, M)
+    assert moved > 50        # the refill does something on these instances
+
+
+def test_gbad_other_baselines_and_errors():
+    # the simultaneous schedule and a forced parallelism as baselines: same rule, same properties
+    rng = np.random.default_rng(77)
+    for _ in range(40):
+        n = int(rng.integers(2, 30))
+        o = rng.integers(1, 30, n).astype(np.int32)
+        s = int(rng.integers(0, 9))
+        M = s + 30 + int(rng.choice([0, 40, 400]))
+        r = O.gbad_simulate(o, s, M, tau0=2, sched=O.SIMS, starts=True)
+        g = O.gba_simulate(o, s, M, 2, O.SIMS)
+        assert (r["start"] <= r["base_start"]).all() and r["flow"] <= g["flow"] and r["peak"] <= M
+        r = O.gbad_simulate(o, s, M, tau0=1, k=2, starts=True)
+        g = O.gba_simulate(o, s, M, 1, O.SPS, 2)
+        assert (r["start"] <= r["base_start"]).all() and r["flow"] <= g["flow"]
+        assert r["peak"] <= max(M, g["peak"])
+    with pytest.raises(O.OracleError) as ei:
+        O.gbad_simulate([3, 200], 0, 100)
+    assert ei.value.code == O.EJOB_INFEASIBLE
+    with pytest.raises(O.OracleError):
+        O.gbad_simulate([3, 0], 0, 100)
+    b = O.gbad_simulate_batch(np.array([[2, 2, 2], [4, 4, 4]], np.int32), 0, 9, [(2, 0, 0), (1, 0, 0)], threads=2)
+    assert b["flow"].tolist() == [[O.gbad_simulate([2, 2, 2], 0, 9, tau0=2)["flow"], O.gbad_simulate([4, 4, 4], 0, 9, tau0=2)["flow"]],
+                                  [O.gbad_simulate([2, 2, 2], 0, 9, tau0=1)["flow"], 15]]
