@@ -88,6 +88,7 @@ extern "C" {
 
 #define KVS_MODE_GBA 0 /* Algorithm 2; with o_est: classes by the estimate        */
 #define KVS_MODE_GSA 1 /* Algorithm 1: every unfinished job in every phase        */
+#define KVS_MODE_GBAD 2 /* Algorithm 2 with dynamic refill ("GBA-D"), see below    */
 
 /* One batch of instances (Section 2.1: jobs with prompt length s and response
  * length o; the estimate is what a non-clairvoyant scheduler believes). */
@@ -110,7 +111,7 @@ typedef struct {
                       eq. (max-parallelism) for SPS, floor(M / (s + tau_p)) for SimS, with s
                       the largest prompt among the phase's jobs, never below 1;
                       > 0: this parallelism in every phase                                  */
-    int32_t mode;  /* KVS_MODE_GBA or KVS_MODE_GSA                                          */
+    int32_t mode;  /* KVS_MODE_GBA, KVS_MODE_GSA or KVS_MODE_GBAD                           */
 } kvs_point_t;
 
 /*
@@ -126,6 +127,22 @@ typedef struct {
  * after the phase begins, completes after o_i rounds if o_i <= tau_p and is
  * otherwise killed at the end of its slice and tried again in the next phase.
  * A phase ends when its last slice ends; a phase without jobs takes no time.
+ *
+ * KVS_MODE_GBAD (appendix "Numerical Experiments", paragraph "Dynamic Refill":
+ * a job is admitted as soon as the pipeline can go on with it without violating
+ * memory feasibility, and never later than in Algorithm 2's schedule; the
+ * paper says no more, this is the rule evaluated).  The baseline is the
+ * schedule of KVS_MODE_GBA at the same (tau0, sched, k) on the true lengths
+ * (o_est is ignored), every job holding its baseline start with its actual run
+ * of o_i rounds.  In the baseline's order (class by class, input order inside a
+ * class) each job moves to the earliest round, not before the start of the job
+ * before it and not after its own baseline start, at which its whole run fits
+ * in every round on top of all other jobs where they stand: the earlier ones
+ * where they were moved to, the later ones at their baseline starts.  This
+ * mode is sequential per instance and keeps the occupancy of every round of
+ * the schedule in LDS: besides the limits above, the baseline may last at most
+ * (about 160 KB - 8 n_jobs) / 4 rounds (KVS_FEASIBLE_ERANGE otherwise), and a
+ * job's cost grows with its length and with the starts it has to try.
  *
  * Outputs (device, [n_pts][n_instances]; job_steps may be NULL):
  *   peak      MemPeak;  feasible  see above;  flow  FlowTime;

@@ -6,8 +6,8 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = [os.path.join(HERE, "csrc", "kvs_kernels.hip"), os.path.join(HERE, "csrc", "kvs_bounds.hip")]
-HEADERS = [os.path.join(HERE, "csrc", h) for h in ("kvs_math.h", "kvs_wave.h", "kvs_phase.h")] + \
+SOURCES = [os.path.join(HERE, "csrc", f) for f in ("kvs_kernels.hip", "kvs_bounds.hip", "kvs_gbad.hip")]
+HEADERS = [os.path.join(HERE, "csrc", h) for h in ("kvs_math.h", "kvs_wave.h", "kvs_phase.h", "kvs_internal.h")] + \
           [os.path.join(ROOT, "include", h) for h in ("kvsched.h", "kvsched_test.h")]
 LIB = os.path.join(HERE, "libkvsched.so")
 

@@ -1,0 +1,377 @@
+/*
+ * kvs_gbad.hip -- Algorithm 2 with dynamic refill ("GBA-D") on gfx950.
+ *
+ * Paper: "Competitive Non-Clairvoyant KV-Cache Scheduling for LLM Inference"
+ * (Feng, Yang, Zhang), appendix "Numerical Experiments", paragraph "Dynamic
+ * Refill": a job is admitted as soon as the pipeline can go on with it without
+ * violating memory feasibility, and no job is later than in the schedule of
+ * Algorithm 2.  The paper gives no more than that; the rule evaluated here:
+ *
+ *   The baseline is Algorithm 2's schedule (classes on the ladder tau_0 * 2^p,
+ *   Procedure 1 or the simultaneous schedule inside a class).  Every job first
+ *   holds its baseline start with its actual run of o_i rounds.  In the
+ *   baseline's order (class by class, input order inside a class) each job
+ *   moves to the earliest round, not before the start of the job before it
+ *   and not after its own baseline start, at which its whole run fits in every
+ *   round (eq. (Memory-Feasibility)) on top of all other jobs where they stand:
+ *   the earlier ones where they were moved, the later ones at their baseline
+ *   starts.  A job can therefore always fall back on its baseline start.
+ *
+ * Unlike the other modes this one is sequential by nature: where a job goes
+ * depends on where all the jobs before it went.  One wavefront evaluates one
+ * (instance, point): the occupancy of every round of the schedule lives in
+ * LDS, a run is taken out, tried and put back 64 rounds at a time, and a start
+ * that fails is not followed by the next round but by the first start that the
+ * failing rounds do not already rule out.
+ */
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <atomic>
+
+#include "kvs_internal.h"
+#include "kvs_math.h"
+#include "kvs_wave.h"
+#include "kvsched.h"
+
+namespace {
+
+constexpr uint32_t kLenMax = 1u << 30;
+constexpr int kLv = 32; /* classes that lengths up to 2^30 can reach on a ladder tau_0 * 2^p */
+
+constexpr uint32_t FLAG_EINVAL = 1u, FLAG_ERANGE = 2u, FLAG_EJOB = 4u;
+
+struct DJobs {
+    const int32_t *o, *s;
+    int32_t n_inst, n_jobs;
+    uint32_t s_scalar;
+    uint32_t cap; /* rounds of the schedule that fit LDS beside the jobs */
+    uint64_t M;
+};
+
+struct DPoints {
+    uint32_t tau0[KVS_MAX_POINTS];
+    uint32_t k[KVS_MAX_POINTS];
+    uint16_t q[KVS_MAX_POINTS]; /* output row */
+    uint8_t sched[KVS_MAX_POINTS];
+    int32_t n;
+};
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+    /* values below 2^31 here */
+    return (uint32_t)wave_max_nonneg((int32_t)v);
+}
+
+__global__ __launch_bounds__(64) void kvs_gbad_kernel(DJobs J, DPoints P, int64_t *peak, uint8_t *feasible,
+                                                      int64_t *flow, int64_t *job_steps)
+{
+    /* dynamic LDS: the jobs in the baseline's order (length, prompt), then the occupancy of
+     * every round */
+    extern __shared__ uint32_t lds[];
+    __shared__ uint32_t cnt[kLv], smax[kLv], off[kLv], tauc[kLv], kc[kLv], beginc[kLv];
+    __shared__ kvs_divisor_t divc[kLv];
+    __shared__ uint32_t flags, horizon;
+
+    const int lane = threadIdx.x;
+    const uint32_t inst = blockIdx.x, pt = blockIdx.y;
+    const uint32_t n = (uint32_t)J.n_jobs;
+    const size_t row = (size_t)inst * n;
+    uint32_t *const ordO = lds, *const ordS = lds + n;
+    int32_t *const occ = reinterpret_cast<int32_t *>(lds + 2u * n);
+    const uint32_t tau0 = P.tau0[pt];
+    const uint32_t lg_tau0 = kvs_ilog2_floor(tau0);
+    const bool sps = P.sched[pt] == KVS_SCHED_SPS;
+
+    if (lane < kLv) {
+        cnt[lane] = 0;
+        smax[lane] = J.s ? 0u : J.s_scalar;
+    }
+    if (lane == 0)
+        flags = 0;
+    __syncthreads();
+
+    /* ---- classes: how many jobs, and the largest prompt ---- */
+    unsigned long long sumO = 0;
+    uint32_t badbits = 0;
+    auto class_of = [&](uint32_t i, uint32_t &o, uint32_t &s) {
+        const int32_t ro = J.o[row + i];
+        const int32_t rs = J.s ? J.s[row + i] : (int32_t)J.s_scalar;
+        uint32_t bad = 0;
+        if (ro < 1 || rs < 0)
+            bad = FLAG_EINVAL;
+        else if ((uint32_t)ro > kLenMax || (uint32_t)rs > kLenMax)
+            bad = FLAG_ERANGE;
+        else if ((uint64_t)(uint32_t)rs + (uint64_t)(uint32_t)ro > J.M)
+            bad = FLAG_EJOB;
+        badbits |= bad;
+        o = ro < 1 ? 1u : ((uint32_t)ro > kLenMax ? kLenMax : (uint32_t)ro);
+        s = rs < 0 ? 0u : ((uint32_t)rs > kLenMax ? kLenMax : (uint32_t)rs);
+        return kvs_class_index(o, tau0, lg_tau0);
+    };
+    for (uint32_t i = (uint32_t)lane; i < n; i += 64) {
+        uint32_t o, s;
+        const uint32_t c = class_of(i, o, s);
+        sumO += o;
+        atomicAdd(&cnt[c], 1u);
+        if (J.s && s > smax[c])
+            atomicMax(&smax[c], s);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        sumO += __shfl_xor(sumO, d, 64);
+        badbits |= __shfl_xor(badbits, d, 64);
+    }
+    __syncthreads();
+
+    /* ---- the baseline's phase table: one lane per class ---- */
+    {
+        uint32_t n_c = 0, err = 0;
+        unsigned long long len = 0;   /* rounds the class lasts */
+        unsigned long long most = 0;  /* bound on what its jobs hold together in a round */
+        if (lane < kLv) {
+            n_c = cnt[lane];
+            const uint64_t tau = (uint64_t)tau0 << lane;
+            uint64_t k = 1;
+            if (n_c > 0) {
+                if (tau * n_c >= (1ull << 31)) {
+                    err = 1;
+                } else {
+                    const uint64_t sm = smax[lane];
+                    if (P.k[pt] > 0)
+                        k = P.k[pt];
+                    else if (sps)
+                        k = kvs_kstar(tau, sm, J.M);
+                    else
+                        k = J.M / (sm + tau);
+                    if (k < 1)
+                        k = 1;
+                    const uint64_t kcap = sps ? tau * n_c : n_c; /* beyond this the offsets no longer change */
+                    if (k > kcap)
+                        k = kcap;
+                    const uint64_t act = k < n_c ? k : n_c;
+                    most = act * (sm + tau + 1u);
+                    if (most >= (1ull << 31))
+                        err = 1;
+                    const uint64_t last = sps ? ((uint64_t)(n_c - 1u) * tau) / k : ((uint64_t)(n_c - 1u) / k) * tau;
+                    len = last + tau;
+                }
+            }
+            tauc[lane] = (uint32_t)(tau > 0xffffffffull ? 0xffffffffull : tau);
+            kc[lane] = (uint32_t)k;
+            divc[lane] = kvs_make_divisor((uint32_t)k);
+        }
+        unsigned long long pre = len; /* inclusive prefix over the classes */
+        uint32_t pre_n = n_c;
+#pragma unroll
+        for (int d = 1; d < kLv; d <<= 1) {
+            const unsigned long long up = __shfl_up(pre, d, 64);
+            const uint32_t un = __shfl_up(pre_n, d, 64);
+            if (lane >= d) {
+                pre += up;
+                pre_n += un;
+            }
+        }
+        /* moved jobs of different classes can share a round: all classes together stay in 31 bits */
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1)
+            most += __shfl_xor(most, d, 64);
+        if (most >= (1ull << 31))
+            err = 1;
+        const unsigned long long total = __shfl(pre, kLv - 1, 64);
+        if (lane < kLv) {
+            beginc[lane] = (uint32_t)(pre - len); /* meaningful only when total fits */
+            off[lane] = pre_n - n_c;
+        }
+        err = __any(err != 0) ? 1u : 0u;
+        if (lane == 0) {
+            uint32_t f = badbits;
+            if (err || total > (unsigned long long)J.cap)
+                f |= 8u; /* this evaluation leaves the range: a class, or the rounds that fit LDS */
+            flags = f;
+            horizon = (uint32_t)(total > (unsigned long long)J.cap ? 0ull : total);
+        }
+    }
+    __syncthreads();
+
+    const uint32_t fl = flags;
+    if (fl != 0) {
+        if (lane == 0) {
+            uint8_t code = KVS_FEASIBLE_ERANGE;
+            if (fl & FLAG_EINVAL)
+                code = KVS_FEASIBLE_EINVAL;
+            else if (fl & FLAG_ERANGE)
+                code = KVS_FEASIBLE_ERANGE;
+            else if (fl & FLAG_EJOB)
+                code = KVS_FEASIBLE_EJOB;
+            const size_t oi = (size_t)P.q[pt] * (size_t)J.n_inst + inst;
+            peak[oi] = -1;
+            feasible[oi] = code;
+            flow[oi] = -1;
+            if (job_steps)
+                job_steps[oi] = -1;
+        }
+        return;
+    }
+    const uint32_t H = horizon;
+
+    /* ---- the jobs in the baseline's order: class by class, input order inside ---- */
+    {
+        uint32_t cur = lane < kLv ? off[lane] : 0u; /* lane c: next free place of class c */
+        for (uint32_t b = 0; b < n; b += 64) {
+            const uint32_t i = b + (uint32_t)lane;
+            const bool act = i < n;
+            uint32_t o = 1, s = 0, c = 0, pos = 0;
+            if (act)
+                c = class_of(i, o, s);
+            uint64_t todo = __ballot(act);
+            while (todo) {
+                const int src = __ffsll((unsigned long long)todo) - 1;
+                const uint32_t c0 = __builtin_amdgcn_readlane(c, src);
+                const uint64_t mk = __ballot(act && c == c0);
+                const uint32_t at = __builtin_amdgcn_readlane(cur, (int)c0);
+                if (act && c == c0)
+                    pos = at + lanes_below(mk);
+                if ((uint32_t)lane == c0)
+                    cur += (uint32_t)__popcll(mk);
+                todo &= ~mk;
+            }
+            if (act) {
+                ordO[pos] = o;
+                ordS[pos] = s + 1u; /* what the job holds in its first round */
+            }
+        }
+        for (uint32_t t = (uint32_t)lane; t < H; t += 64)
+            occ[t] = 0;
+    }
+    __syncthreads();
+
+    /* a run of o rounds from round t, first round s1: added to (sign = 1) or taken out of the rounds */
+    auto ramp = [&](uint32_t t, uint32_t o, uint32_t s1, int32_t sign) {
+        for (uint32_t u = (uint32_t)lane; u < o; u += 64)
+            occ[t + u] += sign * (int32_t)(s1 + u);
+    };
+    /* baseline start of the r-th job of class c */
+    auto base_of = [&](uint32_t c, uint32_t r) {
+        const uint32_t f = sps ? kvs_div(r * tauc[c], divc[c]) : kvs_div(r, divc[c]) * tauc[c];
+        return beginc[c] + f;
+    };
+
+    /* ---- everybody at the baseline start ---- */
+    {
+        uint32_t c = 0, r = 0;
+        for (uint32_t pos = 0; pos < n; pos++) {
+            while (r >= cnt[c]) { /* next class with a job */
+                c++;
+                r = 0;
+            }
+            ramp(base_of(c, r), ordO[pos], ordS[pos], 1);
+            r++;
+        }
+    }
+    __syncthreads();
+
+    /* ---- refill, one job after the other ---- */
+    unsigned long long fsum = 0;
+    {
+        uint32_t c = 0, r = 0, prev = 0;
+        for (uint32_t pos = 0; pos < n; pos++) {
+            while (r >= cnt[c]) {
+                c++;
+                r = 0;
+            }
+            const uint32_t o = ordO[pos], s1 = ordS[pos];
+            const uint32_t base = base_of(c, r);
+            r++;
+            ramp(base, o, s1, -1);
+            __syncthreads();
+            uint32_t t = prev;
+            while (t < base) {
+                /* the first 64 rounds of the run that hold a round over the budget decide how far
+                 * the start has to move: past that round, or far enough to be that much smaller
+                 * in it, whichever comes first; the largest such move over those rounds skips
+                 * only starts that fail in one of them */
+                uint32_t next = 0;
+                for (uint32_t u0 = 0; u0 < o && next == 0; u0 += 64) {
+                    const uint32_t u = u0 + (uint32_t)lane;
+                    uint32_t cand = 0;
+                    if (u < o) {
+                        const int64_t over = (int64_t)occ[t + u] + (int64_t)(s1 + u) - (int64_t)J.M;
+                        if (over > 0)
+                            cand = (over < (int64_t)(u + 1u)) ? t + (uint32_t)over : t + u + 1u;
+                    }
+                    next = wave_max_u32(cand);
+                }
+                if (next == 0)
+                    break; /* fits */
+                t = next;
+            }
+            if (t > base)
+                t = base;
+            ramp(t, o, s1, 1);
+            __syncthreads();
+            prev = t;
+            fsum += (unsigned long long)t + o;
+        }
+    }
+
+    /* ---- the largest occupancy of any round ---- */
+    int32_t pk = 0;
+    for (uint32_t t = (uint32_t)lane; t < H; t += 64)
+        pk = occ[t] > pk ? occ[t] : pk;
+    pk = wave_max_nonneg(pk);
+    if (lane == 0) {
+        const size_t oi = (size_t)P.q[pt] * (size_t)J.n_inst + inst;
+        peak[oi] = pk;
+        feasible[oi] = ((int64_t)pk <= (int64_t)J.M) ? 1 : 0;
+        flow[oi] = (int64_t)fsum;
+        if (job_steps)
+            job_steps[oi] = (int64_t)sumO;
+    }
+}
+
+constexpr size_t kLdsPerGroup = 160 * 1024;
+
+} /* namespace */
+
+int32_t kvs_gbad_run(const kvs_jobs_t *jobs, const kvs_point_t *pts, const int32_t *rows, int32_t n_pts,
+                     int64_t *peak, uint8_t *feasible, int64_t *flow, int64_t *job_steps, void *stream)
+{
+    static std::atomic<int> static_lds{-1};
+    int fixed = static_lds.load(std::memory_order_relaxed);
+    if (fixed < 0) {
+        hipFuncAttributes attr;
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(kvs_gbad_kernel)) != hipSuccess)
+            return KVS_EHIP;
+        fixed = (int)attr.sharedSizeBytes;
+        static_lds.store(fixed, std::memory_order_relaxed);
+    }
+    DJobs J;
+    J.o = jobs->o;
+    J.s = jobs->s;
+    J.n_inst = jobs->n_instances;
+    J.n_jobs = jobs->n_jobs;
+    J.s_scalar = jobs->s ? 0u : (uint32_t)jobs->s_scalar;
+    J.M = (uint64_t)jobs->M;
+    /* all the LDS of a compute unit for one evaluation: the jobs (two words each) and as many
+     * rounds as fit beside them */
+    const size_t room = (kLdsPerGroup - (size_t)fixed) & ~(size_t)15;
+    const size_t for_jobs = sizeof(uint32_t) * 2u * (size_t)jobs->n_jobs;
+    if (for_jobs + 4096 > room)
+        return KVS_ELIMIT;
+    J.cap = (uint32_t)((room - for_jobs) / sizeof(int32_t));
+    DPoints P;
+    P.n = n_pts;
+    for (int32_t j = 0; j < n_pts; j++) {
+        P.tau0[j] = (uint32_t)pts[j].tau0;
+        P.k[j] = (uint32_t)pts[j].k;
+        P.sched[j] = (uint8_t)pts[j].sched;
+        P.q[j] = (uint16_t)rows[j];
+    }
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kvs_gbad_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)room) != hipSuccess)
+        return KVS_EHIP;
+    hipLaunchKernelGGL(kvs_gbad_kernel, dim3((uint32_t)jobs->n_instances, (uint32_t)n_pts), dim3(64), room,
+                       static_cast<hipStream_t>(stream), J, P, peak, feasible, flow, job_steps);
+    return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
+}

@@ -41,6 +41,7 @@
 
 #include "kvsched.h"
 #include "kvsched_test.h"
+#include "kvs_internal.h"
 #include "kvs_math.h"
 #include "kvs_phase.h"
 #include "kvs_wave.h"
@@ -1551,22 +1552,38 @@ int32_t kvs_gba_simulate(const kvs_jobs_t *jobs, const kvs_point_t *pts, int32_t
     if (!peak || !feasible || !flow)
         return KVS_EINVAL;
     HostPoint hp[KVS_MAX_POINTS];
+    kvs_point_t refill[KVS_MAX_POINTS]; /* the points with dynamic refill go to their own kernel */
+    int32_t refill_row[KVS_MAX_POINTS];
+    int32_t n_hp = 0, n_refill = 0;
     for (int32_t q = 0; q < n_pts; q++) {
         const kvs_point_t &p = pts[q];
         if (p.tau0 < 1 || (uint32_t)p.tau0 > kLenMax || p.k < 0 ||
             (p.sched != KVS_SCHED_SPS && p.sched != KVS_SCHED_SIMS) ||
-            (p.mode != KVS_MODE_GBA && p.mode != KVS_MODE_GSA))
+            (p.mode != KVS_MODE_GBA && p.mode != KVS_MODE_GSA && p.mode != KVS_MODE_GBAD))
             return KVS_EINVAL;
-        hp[q].tau0 = (uint32_t)p.tau0;
-        hp[q].k = (uint32_t)p.k;
-        hp[q].sched = p.sched;
-        hp[q].mode = (p.mode == KVS_MODE_GSA) ? MODE_GSA : MODE_GBA;
-        hp[q].q = q;
-        hp[q].ladder = nullptr;
-        hp[q].n_lv = 0;
+        if (p.mode == KVS_MODE_GBAD) {
+            refill[n_refill] = p;
+            refill_row[n_refill++] = q;
+            continue;
+        }
+        hp[n_hp].tau0 = (uint32_t)p.tau0;
+        hp[n_hp].k = (uint32_t)p.k;
+        hp[n_hp].sched = p.sched;
+        hp[n_hp].mode = (p.mode == KVS_MODE_GSA) ? MODE_GSA : MODE_GBA;
+        hp[n_hp].q = q;
+        hp[n_hp].ladder = nullptr;
+        hp[n_hp].n_lv = 0;
+        n_hp++;
     }
     OutsDev out{peak, feasible, flow, job_steps, nullptr};
-    return run_points(to_dev(jobs, true), hp, n_pts, out, static_cast<hipStream_t>(stream));
+    if (n_hp > 0) {
+        rc = run_points(to_dev(jobs, true), hp, n_hp, out, static_cast<hipStream_t>(stream));
+        if (rc != KVS_OK)
+            return rc;
+    }
+    if (n_refill > 0)
+        return kvs_gbad_run(jobs, refill, refill_row, n_refill, peak, feasible, flow, job_steps, stream);
+    return KVS_OK;
 }
 
 int32_t kvs_schedule_eval(const kvs_jobs_t *jobs, const int32_t *tau, const int32_t *k,

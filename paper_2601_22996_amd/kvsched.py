@@ -17,7 +17,7 @@ import torch
 from . import build as _build
 
 SPS, SIMS = 0, 1
-MODE_GBA, MODE_GSA = 0, 1
+MODE_GBA, MODE_GSA, MODE_GBAD = 0, 1, 2
 FEASIBLE_EJOB, FEASIBLE_EINVAL, FEASIBLE_ERANGE = 0xFC, 0xFE, 0xFF
 OK, EINVAL, EJOB_INFEASIBLE, ERANGE, EHIP, ELIMIT = 0, 1, 2, 3, 4, 5
 MAX_JOBS, MAX_POINTS, MAX_LEVELS = 16384, 64, 64

@@ -22,7 +22,7 @@ import numpy as np
 
 BLOCK = 256
 SPS, SIMS = 0, 1
-MODE_GBA, MODE_GSA = 0, 1
+MODE_GBA, MODE_GSA, MODE_GBAD = 0, 1, 2
 
 
 @dataclass(frozen=True)

@@ -408,6 +408,79 @@ def test_estimate_rule_hand_worked_cases(K):
             assert int(got[key][0, 0]) == case["want"][key], (key, case)
 
 
+# ---------------------------------------------------------------------------
+# Algorithm 2 with dynamic refill (KVS_MODE_GBAD)
+# ---------------------------------------------------------------------------
+def oracle_gbad(o, s, M, pts):
+    return O.gbad_simulate_batch(o, s, M, [(t, sc, k) for t, sc, k, _ in pts], threads=THREADS)
+
+
+def test_gbad_hand_worked_cases(K):
+    # the cases worked by hand in tests/test_oracle_pins.py
+    for o, s, M, tau0, flow, peak in [([2, 2, 2], 0, 4, 2, 8, 4), ([1, 4, 3, 2], 1, 10, 4, 10, 9),
+                                      ([4, 4, 4], 0, 9, 1, 15, 9), ([5] * 15, 0, 15, 5, 180, 15)]:
+        got = run_gba(K, np.asarray([o], np.int32), s, M, [(tau0, 0, 0, K.MODE_GBAD), (tau0, 0, 0, K.MODE_GBA)])
+        assert (got["flow"][0, 0], got["peak"][0, 0], got["feasible"][0, 0]) == (flow, peak, 1)
+        assert got["flow"][0, 0] <= got["flow"][1, 0] and got["job_steps"][0, 0] == sum(o)
+
+
+@pytest.mark.parametrize("n,I,hetero,omax", [(1, 4, False, 9), (2, 6, True, 9), (63, 6, False, 40), (64, 5, True, 40),
+                                            (65, 5, False, 300), (200, 6, True, 120), (1000, 4, False, 500),
+                                            (1500, 3, True, 60), (3000, 2, False, 200)])
+def test_gbad_random_instances(K, n, I, hetero, omax):
+    rng = np.random.default_rng(77 * n + I)
+    o = np.minimum(rng.geometric(1.0 / max(2, omax // 4), (I, n)), omax).astype(np.int32)
+    s = rng.integers(0, 60, (I, n)).astype(np.int32) if hetero else int(rng.integers(0, 60))
+    # the whole baseline schedule has to fit LDS (some 35000 rounds): the larger instances get budgets and
+    # forced parallelisms that keep enough jobs in flight
+    M = int(omax + 60 + rng.choice([0, 40, 700, 6000] if n <= 200 else [20000, 60000]))
+    k1, k2 = max(3, n // 20), max(2, n // 10)
+    pts = [(1, 0, 0, K.MODE_GBAD), (2, 0, 0, K.MODE_GBAD), (3, 1, 0, K.MODE_GBAD), (8, 0, 0, K.MODE_GBAD),
+           (1, 0, k1, K.MODE_GBAD), (4, 1, k2, K.MODE_GBAD), (1, 0, 100000, K.MODE_GBAD)]
+    got = run_gba(K, o, s, M, pts)
+    assert_same(got, oracle_gbad(o, s, M, pts))
+    # in one call with the other modes: rows keep their places
+    mixed = [(1, 0, 0, K.MODE_GBA), pts[0], (2, 1, 0, K.MODE_GSA), pts[2], (1, 0, 0, K.MODE_GBA)]
+    got2 = run_gba(K, o, s, M, mixed)
+    ref = O.gba_simulate_batch(o, s, M, [mixed[0], mixed[2], mixed[4]])
+    assert_same({k: v[[0, 2, 4]] for k, v in got2.items()}, ref)
+    assert_same({k: v[[1, 3]] for k, v in got2.items()}, {k: v[[0, 2]] for k, v in got.items()})
+    # never worse than the baseline, never above the budget where the baseline is not
+    assert (got2["flow"][1] <= got2["flow"][0]).all() and (got2["peak"][1] <= M).all()
+
+
+@pytest.mark.parametrize("cfg,count", [(2, 96), (3, 64)])
+def test_gbad_on_the_workloads(K, cfg, count):
+    w = W.WORKLOADS[cfg]
+    d = W.generate(w, 0, count, threads=8)
+    sarg = d["s"] if d["s"] is not None else d["s_scalar"]
+    pts = [(t, sc, 0, K.MODE_GBAD) for t, sc, _, _ in w.sweep()]
+    got = run_gba(K, d["o"], sarg, d["M"], pts)
+    assert_same(got, oracle_gbad(d["o"], sarg, d["M"], pts))
+    base = run_gba(K, d["o"], sarg, d["M"], w.sweep())
+    assert (got["flow"] <= base["flow"]).all() and (got["flow"] < base["flow"]).any()
+    assert (got["peak"] <= d["M"]).all() and (got["feasible"] == 1).all()
+
+
+def test_gbad_in_band_errors(K):
+    o = np.array([[5, 5, 5], [5, 0, 5], [5, 500, 5], [5, 5, 5]], np.int32)
+    got = run_gba(K, o, 10, 100, [(1, 0, 0, K.MODE_GBAD)])
+    assert got["feasible"][0].tolist() == [1, K.FEASIBLE_EINVAL, K.FEASIBLE_EJOB, 1]
+    assert got["flow"][0, 1] == -1 and got["peak"][0, 2] == -1
+    # a baseline that lasts longer than the rounds LDS can hold: 60 jobs of 30000 rounds, one at a time
+    o = np.full((2, 60), 30000, np.int32)
+    o[1] = 300
+    got = run_gba(K, o, 0, 40000, [(1, 0, 1, K.MODE_GBAD), (1, 0, 0, K.MODE_GBAD)])
+    assert got["feasible"][0].tolist() == [K.FEASIBLE_ERANGE, 1] and got["flow"][0, 0] == -1
+    assert got["flow"][0, 1] == O.gbad_simulate(o[1], 0, 40000, tau0=1, k=1)["flow"]
+    assert got["feasible"][1, 0] == K.FEASIBLE_ERANGE     # also with the automatic parallelism (2 jobs in flight)
+    # the largest instance size
+    rng = np.random.default_rng(9)
+    o = rng.integers(1, 20, (1, K.MAX_JOBS)).astype(np.int32)
+    pts = [(1, 0, 0, K.MODE_GBAD)]
+    assert_same(run_gba(K, o, 3, 4000, pts), oracle_gbad(o, 3, 4000, pts))
+
+
 def test_calls_on_a_side_stream_and_reused_outputs(K):
     # the work goes to the stream that is passed; outputs allocated once are refilled in place
     rng = np.random.default_rng(2718)
