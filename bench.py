@@ -101,7 +101,10 @@ def cpu_baseline(w, pts, target_seconds, threads, gpu_head):
     kept = []
 
     def run(i0, i1):
-        r = O.gba_simulate_batch(d["o"], sarg, d["M"], pts, d["o_est"], i0, i1)
+        if w.mode == W.MODE_GBAD:
+            r = O.gbad_simulate_batch(d["o"], sarg, d["M"], [tuple(p[:3]) for p in pts], i0, i1)
+        else:
+            r = O.gba_simulate_batch(d["o"], sarg, d["M"], pts, d["o_est"], i0, i1)
         kept.append((i0, i1, r))
         return int(r["job_steps"].sum())
 
@@ -251,8 +254,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the largest sweep)")
     ap.add_argument("--instances", type=int, default=0, help="override the workload's number of instances")
     ap.add_argument("--jobs", type=int, default=0, help="override the workload's jobs per instance")
-    ap.add_argument("--mode", choices=["workload", "gsa"], default="workload",
-                    help="gsa: the workload's sweep in GSA mode (Algorithm 1: every unfinished job in every phase)")
+    ap.add_argument("--mode", choices=["workload", "gsa", "gbad"], default="workload",
+                    help="gsa: the workload's sweep in GSA mode (Algorithm 1: every unfinished job in every phase); "
+                         "gbad: with dynamic refill (GBA-D)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="wall time of the oracle baseline (half on one core, half on all threads); 0 skips it")
     ap.add_argument("--threads", type=int, default=min(16, os.cpu_count() or 1))
     ap.add_argument("--path", choices=["sweep", "bounds", "opt_perm"], default="sweep",
@@ -284,6 +288,8 @@ def main():
         w = dataclasses.replace(w, name=f"{w.name}_{w.n_instances}x{w.n_jobs}")
     if args.mode == "gsa":
         w = dataclasses.replace(w, mode=W.MODE_GSA, name=w.name + "_gsa")
+    if args.mode == "gbad":
+        w = dataclasses.replace(w, mode=W.MODE_GBAD, estimates=False, name=w.name + "_gbad")
     pts = w.sweep()
     o, s, e = load_workload(w, torch, args.threads)
     sarg = s if s is not None else w.s_scalar
@@ -343,10 +349,14 @@ def main():
         # second.  It is NOT the utilisation of the memory bus: the kernel reads an instance once for all
         # its sweep points (`hbm_physical_frac`), and what it runs into is the issue rate of integer
         # vector instructions (`bound`, `valu_issue_frac`).
-        "roofline": {"bound": "alu", "bound_detail": "valu-issue (integer vector instructions), then the LDS pipeline",
+        "roofline": {"bound": "alu",
+                     "bound_detail": ("latency of dependent LDS operations: one wavefront per evaluation, sequential by nature"
+                                      if w.mode == W.MODE_GBAD else
+                                      "valu-issue (integer vector instructions), then the LDS pipeline"),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "kvs_sweep_kernel", "kernel_ms": kern_ms, "kernel_ms_is": "median of the steps",
+                     "kernel": "kvs_gbad_kernel" if w.mode == W.MODE_GBAD else "kvs_sweep_kernel",
+                     "kernel_ms": kern_ms, "kernel_ms_is": "median of the steps",
                      "algorithmic_bytes_per_launch": alg_bytes,
                      # the fused kernel reads an instance once per launch, not once per point
                      "fused_bytes_per_launch": fused_bytes,

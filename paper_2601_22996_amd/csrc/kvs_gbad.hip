@@ -46,6 +46,8 @@ struct DJobs {
     int32_t n_inst, n_jobs;
     uint32_t s_scalar;
     uint32_t cap; /* rounds of the schedule that fit LDS beside the jobs */
+    uint32_t tier; /* 0: an evaluation that needs more rounds is left to the next launch; 1: that launch,
+                      which takes only those; 2: the only launch                                        */
     uint64_t M;
 };
 
@@ -56,6 +58,17 @@ struct DPoints {
     uint8_t sched[KVS_MAX_POINTS];
     int32_t n;
 };
+
+/* What this wavefront wrote to LDS is seen by its later reads, whichever lane did either: a
+ * workgroup here is one wavefront, whose LDS operations are carried out in order. */
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+constexpr uint8_t FEASIBLE_PENDING = 0xFD; /* internal: left for the launch with all of LDS */
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
@@ -75,6 +88,8 @@ __global__ __launch_bounds__(64) void kvs_gbad_kernel(DJobs J, DPoints P, int64_
 
     const int lane = threadIdx.x;
     const uint32_t inst = blockIdx.x, pt = blockIdx.y;
+    if (J.tier == 1 && feasible[(size_t)P.q[pt] * (size_t)J.n_inst + inst] != FEASIBLE_PENDING)
+        return; /* done by the launch before */
     const uint32_t n = (uint32_t)J.n_jobs;
     const size_t row = (size_t)inst * n;
     uint32_t *const ordO = lds, *const ordS = lds + n;
@@ -186,8 +201,10 @@ __global__ __launch_bounds__(64) void kvs_gbad_kernel(DJobs J, DPoints P, int64_
         err = __any(err != 0) ? 1u : 0u;
         if (lane == 0) {
             uint32_t f = badbits;
-            if (err || total > (unsigned long long)J.cap)
-                f |= 8u; /* this evaluation leaves the range: a class, or the rounds that fit LDS */
+            if (err)
+                f |= 8u; /* this evaluation leaves the range in some class */
+            else if (total > (unsigned long long)J.cap)
+                f |= (J.tier == 0 && f == 0) ? 16u : 8u; /* more rounds than fit: the next launch has more room, or none has */
             flags = f;
             horizon = (uint32_t)(total > (unsigned long long)J.cap ? 0ull : total);
         }
@@ -198,6 +215,8 @@ __global__ __launch_bounds__(64) void kvs_gbad_kernel(DJobs J, DPoints P, int64_
     if (fl != 0) {
         if (lane == 0) {
             uint8_t code = KVS_FEASIBLE_ERANGE;
+            if (fl == 16u)
+                code = FEASIBLE_PENDING;
             if (fl & FLAG_EINVAL)
                 code = KVS_FEASIBLE_EINVAL;
             else if (fl & FLAG_ERANGE)
@@ -283,8 +302,6 @@ __global__ __launch_bounds__(64) void kvs_gbad_kernel(DJobs J, DPoints P, int64_
             const uint32_t o = ordO[pos], s1 = ordS[pos];
             const uint32_t base = base_of(c, r);
             r++;
-            ramp(base, o, s1, -1);
-            __syncthreads();
             uint32_t t = prev;
             while (t < base) {
                 /* the first 64 rounds of the run that hold a round over the budget decide how far
@@ -296,7 +313,11 @@ __global__ __launch_bounds__(64) void kvs_gbad_kernel(DJobs J, DPoints P, int64_
                     const uint32_t u = u0 + (uint32_t)lane;
                     uint32_t cand = 0;
                     if (u < o) {
-                        const int64_t over = (int64_t)occ[t + u] + (int64_t)(s1 + u) - (int64_t)J.M;
+                        /* what the others hold in that round: the job's own run, still at its baseline
+                         * start, is taken off */
+                        const uint32_t x = t + u;
+                        const int64_t own = (x >= base) ? (int64_t)(s1 + (x - base)) : 0; /* x < base + o: t < base */
+                        const int64_t over = (int64_t)occ[x] - own + (int64_t)(s1 + u) - (int64_t)J.M;
                         if (over > 0)
                             cand = (over < (int64_t)(u + 1u)) ? t + (uint32_t)over : t + u + 1u;
                     }
@@ -306,10 +327,14 @@ __global__ __launch_bounds__(64) void kvs_gbad_kernel(DJobs J, DPoints P, int64_
                     break; /* fits */
                 t = next;
             }
-            if (t > base)
+            if (t < base) { /* it moves */
+                ramp(base, o, s1, -1);
+                wave_sync();
+                ramp(t, o, s1, 1);
+                wave_sync();
+            } else {
                 t = base;
-            ramp(t, o, s1, 1);
-            __syncthreads();
+            }
             prev = t;
             fsum += (unsigned long long)t + o;
         }
@@ -353,13 +378,17 @@ int32_t kvs_gbad_run(const kvs_jobs_t *jobs, const kvs_point_t *pts, const int32
     J.n_jobs = jobs->n_jobs;
     J.s_scalar = jobs->s ? 0u : (uint32_t)jobs->s_scalar;
     J.M = (uint64_t)jobs->M;
-    /* all the LDS of a compute unit for one evaluation: the jobs (two words each) and as many
-     * rounds as fit beside them */
+    /* Two launches.  The first gives an evaluation a third of a compute unit's LDS (the jobs, two
+     * words each, and the rounds that fit beside them: about 10 000 rounds for 1 000 jobs), so that
+     * three share a compute unit -- an evaluation is one wavefront working through dependent LDS
+     * operations, and only company hides that; an evaluation whose baseline lasts longer marks
+     * itself, and the second launch, with all the LDS of a compute unit for one evaluation, takes
+     * only those.  Instances too large for the first go straight to the second. */
     const size_t room = (kLdsPerGroup - (size_t)fixed) & ~(size_t)15;
+    const size_t small = ((kLdsPerGroup / 3) - (size_t)fixed - 64) & ~(size_t)15;
     const size_t for_jobs = sizeof(uint32_t) * 2u * (size_t)jobs->n_jobs;
     if (for_jobs + 4096 > room)
         return KVS_ELIMIT;
-    J.cap = (uint32_t)((room - for_jobs) / sizeof(int32_t));
     DPoints P;
     P.n = n_pts;
     for (int32_t j = 0; j < n_pts; j++) {
@@ -371,7 +400,19 @@ int32_t kvs_gbad_run(const kvs_jobs_t *jobs, const kvs_point_t *pts, const int32
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kvs_gbad_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)room) != hipSuccess)
         return KVS_EHIP;
-    hipLaunchKernelGGL(kvs_gbad_kernel, dim3((uint32_t)jobs->n_instances, (uint32_t)n_pts), dim3(64), room,
-                       static_cast<hipStream_t>(stream), J, P, peak, feasible, flow, job_steps);
+    const dim3 grid((uint32_t)jobs->n_instances, (uint32_t)n_pts);
+    const bool two = for_jobs + 8192 <= small;
+    if (two) {
+        J.cap = (uint32_t)((small - for_jobs) / sizeof(int32_t));
+        J.tier = 0;
+        hipLaunchKernelGGL(kvs_gbad_kernel, grid, dim3(64), small, static_cast<hipStream_t>(stream), J, P, peak,
+                           feasible, flow, job_steps);
+        if (hipGetLastError() != hipSuccess)
+            return KVS_EHIP;
+    }
+    J.cap = (uint32_t)((room - for_jobs) / sizeof(int32_t));
+    J.tier = two ? 1u : 2u;
+    hipLaunchKernelGGL(kvs_gbad_kernel, grid, dim3(64), room, static_cast<hipStream_t>(stream), J, P, peak, feasible,
+                       flow, job_steps);
     return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
 }
