@@ -77,6 +77,9 @@ constexpr int MODE_GBA = 0, MODE_GSA = 1, MODE_SINGLE = 2;
  *           leave behind because a value is too wide for their one-word entries.
  * The first four read the jobs from memory once (STREAM: once per batch of phases).
  */
+#ifndef KVS_DEEP
+#define KVS_DEEP 4
+#endif
 constexpr int KIND_NESTED = 0, KIND_ALIVE = 1, KIND_GATHER = 2, KIND_STREAM = 3, KIND_WIDE = 4;
 
 struct JobsDev {
@@ -214,6 +217,7 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
     constexpr bool ALIVE = KIND == KIND_ALIVE;
     constexpr bool GATHERS = KIND == KIND_GATHER || KIND == KIND_STREAM;
     constexpr bool COPY = KIND == KIND_GATHER;   /* the instance is kept in LDS beside the phase buffer */
+    static_assert(!GATHERS || PACKED, "the gathered entries are written as one word");
 
     /* Dynamic LDS.  Phase entries: n_jobs words, twice that when !PACKED.  COPY: behind them
      * the instance in input order, one word per job (prompt << 16 | length with per-job prompts,
@@ -356,20 +360,28 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                 q.e = want_e ? *reinterpret_cast<const int4 *>(J.e + row + i) : make_int4(1, 1, 1, 1);
                 return q;
             };
-            Quad nxt;
-            nxt.o = nxt.s = nxt.e = make_int4(1, 1, 1, 1);
-            if (seg_lo + 4u * lane < seg_hi)
-                nxt = load4(seg_lo + 4u * lane);
-            for (uint32_t base = seg_lo; base < seg_hi; base += 256) {
-                const uint32_t i = base + 4u * (uint32_t)lane;
-                const Quad cur = nxt;
-                if (i + 256 < seg_hi) /* the next chunk's loads fly while this one is classified */
-                    nxt = load4(i + 256);
-                if (i < seg_hi) {
-                    account(RawJob{cur.o.x, cur.s.x, cur.e.x}, i);
-                    account(RawJob{cur.o.y, cur.s.y, cur.e.y}, i + 1);
-                    account(RawJob{cur.o.z, cur.s.z, cur.e.z}, i + 2);
-                    account(RawJob{cur.o.w, cur.s.w, cur.e.w}, i + 3);
+            /* The loads of kDeep chunks are issued before the first is looked at: a segment is
+             * only a few chunks long, and a workgroup in this pass has nothing else to wait with
+             * (the registers are free: the evaluation's are not live yet). */
+            constexpr uint32_t kDeep = KVS_DEEP;
+            for (uint32_t base = seg_lo; base < seg_hi; base += 256u * kDeep) {
+                Quad q[kDeep];
+#pragma unroll
+                for (uint32_t dch = 0; dch < kDeep; dch++) {
+                    const uint32_t i = base + 256u * dch + 4u * (uint32_t)lane;
+                    q[dch].o = q[dch].s = q[dch].e = make_int4(1, 1, 1, 1);
+                    if (i < seg_hi)
+                        q[dch] = load4(i);
+                }
+#pragma unroll
+                for (uint32_t dch = 0; dch < kDeep; dch++) {
+                    const uint32_t i = base + 256u * dch + 4u * (uint32_t)lane;
+                    if (i < seg_hi) {
+                        account(RawJob{q[dch].o.x, q[dch].s.x, q[dch].e.x}, i);
+                        account(RawJob{q[dch].o.y, q[dch].s.y, q[dch].e.y}, i + 1);
+                        account(RawJob{q[dch].o.z, q[dch].s.z, q[dch].e.z}, i + 2);
+                        account(RawJob{q[dch].o.w, q[dch].s.w, q[dch].e.w}, i + 3);
+                    }
                 }
             }
         } else {
@@ -594,7 +606,7 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
             else if (sps)
                 k = kvs_kstar(tau, smax, J.M);
             else
-                k = J.M / (smax + tau);
+                k = kvs_udiv(J.M, smax + tau);
             if (k < 1)
                 k = 1;
             const uint64_t kcap = sps ? tau * np : np; /* beyond this the offsets no longer change */
@@ -638,7 +650,7 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
             if (sps) {
                 sumF0 = kvs_floor_sum(sl.n, sc.k, sl.tau);
             } else {
-                const uint64_t q = sl.n / sc.k, rem = sl.n - q * sc.k; /* q whole batches, then rem jobs */
+                const uint64_t q = kvs_div(sl.n, sc.div), rem = sl.n - q * sc.k; /* q whole batches, then rem jobs */
                 sumF0 = (uint64_t)sl.tau * ((uint64_t)sc.k * (q * (q - 1u) / 2u) + q * rem);
             }
         }
@@ -750,13 +762,13 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
      */
     auto gather = [&](uint32_t b0, uint32_t b1) {
         const uint32_t g_cnt = b1 - b0; /* at most 64 */
-        uint32_t my_lv = 0, my_level = 0, my_tau = 0, my_below = 0, my_cur = 0;
+        uint32_t my_info = 0, my_tau = 0, my_cur = 0; /* info: the slot's level, bit 8: it is a level's own phase */
         if ((uint32_t)lane < g_cnt) {
             const uint32_t si = order[b0 + (uint32_t)lane];
-            my_level = si < (uint32_t)kLevels ? 1u : 0u;
-            my_lv = my_level ? si : (uint32_t)G.m[si - kLevels];
+            const uint32_t my_level = si < (uint32_t)kLevels ? 1u : 0u;
+            const uint32_t my_lv = my_level ? si : (uint32_t)G.m[si - kLevels];
+            my_info = my_lv | (my_level << 8);
             my_tau = lad[my_lv];
-            my_below = my_lv ? lad[my_lv - 1u] : 0u;
             my_cur = slot[si].off;
             for (int w = 0; w < wave; w++) {
                 uint32_t c = cumE[w][my_lv];
@@ -802,10 +814,10 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
              * the levels at which some of them is still unfinished: a job that enters at ga and
              * has the length o is there at the levels ga .. max(ga, level of o) */
             uint64_t here; /* bit l: some job takes part at level l; its lowest bit: the lowest entry level */
+            bool ok = true; /* checked in pass 1 */
+            const uint32_t go = act ? level_of<EXPLICIT>(o, G, lad, ok) : 0u; /* completes at this level ... */
+            const uint32_t gb = go > ga ? go : ga;                            /* ... but not before it enters */
             {
-                bool ok = true; /* checked in pass 1 */
-                const uint32_t go = act ? level_of<EXPLICIT>(o, G, lad, ok) : 0u;
-                const uint32_t gb = go > ga ? go : ga;
                 const uint64_t mine =
                     act ? (((gb >= 63u) ? ~0ull : ((2ull << gb) - 1ull)) & ~((1ull << ga) - 1ull)) : 0ull;
                 here = (uint64_t)wave_or((uint32_t)mine);
@@ -813,25 +825,28 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                     here |= (uint64_t)wave_or((uint32_t)(mine >> 32)) << 32;
             }
             const uint32_t ga_min = here ? (uint32_t)__builtin_ctzll(here) : 0xffffffffu;
+            const uint32_t ga_act = act ? ga : 0xffffffffu;          /* a lane without a job enters nowhere */
+            const uint32_t s_part = F.has_s ? (s << F.sshift) : 0u; /* the entry's prompt field */
             for (uint32_t j = 0; j < g_cnt; j++) {
-                const uint32_t lv = __builtin_amdgcn_readlane(my_lv, (int)j);
-                const uint32_t level = __builtin_amdgcn_readlane(my_level, (int)j);
+                const uint32_t info = __builtin_amdgcn_readlane(my_info, (int)j);
+                const uint32_t lv = info & 0xffu;
+                const bool level = (info >> 8) != 0;
                 if (level ? !((here >> lv) & 1ull) : (ga_min > lv))
                     continue; /* none of these jobs is in that phase */
-                const uint32_t tau_lv = __builtin_amdgcn_readlane(my_tau, (int)j);
-                const uint32_t tau_below = __builtin_amdgcn_readlane(my_below, (int)j);
                 /* entered by now; and, for a level's own phase, not through before it */
-                const bool take = act && ga <= lv && (!level || ga == lv || o > tau_below);
+                const uint32_t stays = level ? gb : 0xffffffffu;
+                const bool take = ga_act <= lv && stays >= lv;
                 const uint64_t bal = __ballot(take);
                 if (bal == 0)
                     continue;
+                const uint32_t tau_lv = __builtin_amdgcn_readlane(my_tau, (int)j);
                 const uint32_t at = __builtin_amdgcn_readlane(my_cur, (int)j);
-                if (take) {
-                    const bool done = o <= tau_lv;
-                    put_entry<PACKED>(buf, n, at + lanes_below(bal), done ? o : tau_lv, done, s, F);
+                if (take) { /* the entry: duration | done | prompt (one word here) */
+                    const bool done = go <= lv;
+                    buf[at + lanes_below(bal)] = (done ? (o | (1u << F.dbits)) : tau_lv) | s_part;
                 }
                 if ((uint32_t)lane == j)
-                    my_cur += (uint32_t)__popcll(bal);
+                    my_cur = at + (uint32_t)__popcll(bal);
             }
           }
         }

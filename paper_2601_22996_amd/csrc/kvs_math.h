@@ -60,6 +60,26 @@ KVS_HD uint32_t kvs_class_index(uint32_t x, uint32_t tau0, uint32_t lg_tau0)
 }
 
 /*
+ * floor(a / b) for a < 2^63 and 1 <= b < 2^53 whose quotient is below 2^52: one double-precision
+ * division and a correction by at most one.  (The quotient of the two roundings and of the
+ * division itself is off by less than 1; the remainder, in wrapping 64-bit arithmetic, says
+ * which way.)  On the GPU a 64-bit integer division is some hundred instructions of one
+ * wavefront while the others wait for the phase tables; this is a dozen.
+ */
+KVS_HD uint64_t kvs_udiv(uint64_t a, uint64_t b)
+{
+    uint64_t q = (uint64_t)((double)a / (double)b);
+    int64_t r = (int64_t)(a - q * b);
+    if (r < 0) {
+        q -= 1u;
+        r += (int64_t)b;
+    }
+    if ((uint64_t)r >= b)
+        q += 1u;
+    return q;
+}
+
+/*
  * Level of a length x on an explicit ladder lad[0] <= lad[1] <= ... <= lad[n_lv - 1]
  * (1 <= n_lv <= 64): the number of slices below x, which is the index of the first slice
  * that covers x, or n_lv when none does.  Six halving steps find the largest p <= 63 whose
@@ -100,7 +120,7 @@ KVS_HD kvs_divisor_t kvs_make_divisor(uint32_t d)
         return r;
     }
     uint32_t l = 32u - kvs_clz32(d - 1u); /* ceil(log2 d), >= 1 */
-    r.mul = (uint32_t)((((uint64_t)1) << (31u + l)) / d) + 1u;
+    r.mul = (uint32_t)kvs_udiv(((uint64_t)1) << (31u + l), d) + 1u;
     r.shift = l - 1u;
     return r;
 }
@@ -110,14 +130,25 @@ KVS_HD uint32_t kvs_div(uint32_t x, kvs_divisor_t d)
     return d.mul ? (kvs_mulhi32(x, d.mul) >> d.shift) : x;
 }
 
-KVS_HD uint64_t kvs_gcd64(uint64_t a, uint64_t b)
+/* gcd(a, b) for a >= 1, by halving and subtracting (no division). */
+KVS_HD uint32_t kvs_gcd32(uint32_t a, uint32_t b)
 {
-    while (b != 0) {
-        uint64_t r = a % b;
-        a = b;
-        b = r;
+    if (b == 0)
+        return a;
+    const uint32_t za = 31u - kvs_clz32(a & (0u - a)), zb = 31u - kvs_clz32(b & (0u - b)); /* trailing zeros */
+    const uint32_t shift = za < zb ? za : zb;
+    a >>= za;
+    b >>= zb;
+    while (a != b) { /* both odd */
+        if (a > b) {
+            a -= b;
+            a >>= 31u - kvs_clz32(a & (0u - a));
+        } else {
+            b -= a;
+            b >>= 31u - kvs_clz32(b & (0u - b));
+        }
     }
-    return a;
+    return a << shift;
 }
 
 /*
@@ -133,11 +164,13 @@ KVS_HD uint64_t kvs_gcd64(uint64_t a, uint64_t b)
 KVS_HD uint64_t kvs_kstar(uint64_t tau, uint64_t s, uint64_t M)
 {
     uint64_t den = 2u * s + tau + 1u;
-    uint64_t K = (2u * M) / den;
+    uint64_t K = kvs_udiv(2u * M, den);
     if (K == 0)
         return 0;
+    /* gcd(tau, K) = gcd(tau, K mod tau); tau is below 2^32 wherever this is called */
+    const uint64_t g = kvs_gcd32((uint32_t)tau, (uint32_t)(K - kvs_udiv(K, tau) * tau));
     /* K * den <= 2M always; compare without forming a negative right side */
-    if (K * den + tau <= 2u * M + kvs_gcd64(tau, K))
+    if (K * den + tau <= 2u * M + g)
         return K;
     return K - 1u;
 }
@@ -155,18 +188,20 @@ KVS_HD uint64_t kvs_floor_sum(uint64_t n, uint64_t k, uint64_t tau)
     uint64_t ans = 0, a = tau, m = k, b = 0;
     for (;;) {
         if (a >= m) {
-            ans += (n - 1u) * n / 2u * (a / m);
-            a %= m;
+            const uint64_t q = kvs_udiv(a, m);
+            ans += (n - 1u) * n / 2u * q;
+            a -= q * m;
         }
         if (b >= m) {
-            ans += n * (b / m);
-            b %= m;
+            const uint64_t q = kvs_udiv(b, m);
+            ans += n * q;
+            b -= q * m;
         }
         uint64_t y = a * n + b;
         if (y < m)
             return ans;
-        n = y / m;
-        b = y % m;
+        n = kvs_udiv(y, m);
+        b = y - n * m;
         uint64_t t = m;
         m = a;
         a = t;
