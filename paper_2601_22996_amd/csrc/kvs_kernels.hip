@@ -597,6 +597,7 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
         sc.S = 64;
         sc.nslab = 0;
         sc.bad = 0;
+        sc.narrow = 0;
         sc.div = kvs_make_divisor(1);
         if (sl.n > 0) {
             const uint64_t tau = sl.tau, smax = sl.smax, np = sl.n;
@@ -613,8 +614,13 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
             if (k > kcap)
                 k = kcap;
             const uint64_t act = (k < np) ? k : np;
-            if (act * (smax + tau + WIN + 1) >= (1ull << 31)) /* window sums stay in 32 bits */
+            if (act * (smax + tau + 2 * WIN + 1) >= (1ull << 31)) /* window sums stay in 32 bits */
                 sc.bad = 1;
+            /* Every event of a round weighs at most smax + 1 + tau + (rounds of a slab) either way, and
+             * at most `act` runs start and at most `act` end in one round: if that leaves a round's
+             * sums within 23 and 9 signed bits, the phase is evaluated in narrow windows. */
+            sc.narrow = (act < 256u && 2u * act * (smax + tau + 2 * WIN + 1) < (1ull << 22)) ? 1u : 0u;
+            const uint32_t wcap = sc.narrow ? 2u * (uint32_t)WIN : (uint32_t)WIN;
             sc.k = (uint32_t)k;
             sc.div = kvs_make_divisor(sc.k);
             sc.H = start_offset(sl.n - 1, sl.tau, sc, sps) + sl.tau;
@@ -622,8 +628,8 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
              * slabs repeat less work at their edges, and that outweighs the balance);
              * SimS batches do not overlap, so whole batches per slab need no carry-in */
             uint32_t S = ((2 * sc.H + NW - 1) / NW + 63u) & ~63u;
-            S = S > (uint32_t)WIN ? (uint32_t)WIN : S;
-            if (!sps && sl.tau <= (uint32_t)WIN) {
+            S = S > wcap ? wcap : S;
+            if (!sps && sl.tau <= wcap) {
                 uint32_t b = S / sl.tau;
                 S = sl.tau * (b ? b : 1u);
             }
@@ -685,8 +691,10 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                 for (uint32_t j = first; j < items; j += NW) {
                     if (sc.S == 0)
                         eval_thin<PACKED>(sl, sc, sps, j, buf, n, J.s_scalar, F, lane, pk, sumF);
+                    else if (sc.narrow)
+                        eval_slab<PACKED, WIN, true>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk, sumF);
                     else
-                        eval_slab<PACKED, WIN>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk, sumF);
+                        eval_slab<PACKED, WIN, false>(sl, sc, sps, j, buf, n, J.s_scalar, F, ev[wave], lane, pk, sumF);
                 }
             }
             pk = wave_max_nonneg(pk);

@@ -40,6 +40,7 @@ struct Sched {
     uint32_t nslab; /* work items: slabs of S rounds, groups of 64 runs, 1 for a phase of at most
                        64 runs, 0 when there is nothing to evaluate        */
     uint32_t bad;   /* the window sums could leave 32 bits: not evaluated  */
+    uint32_t narrow; /* the event sums of a round fit one 32-bit word (see WinFmt): slabs twice as long */
     kvs_divisor_t div;
 };
 
@@ -135,22 +136,59 @@ __device__ __forceinline__ void get_entry(const uint32_t *buf, uint32_t n_cap, u
 constexpr unsigned long long kEndOne = 0xffffffff00000000ull;
 
 /*
+ * The entry of a round in a wavefront's window: the number of runs that start there minus those
+ * whose first round off it is, C, above the sum A of their weights (s + 1 - start offset, signed),
+ * in one integer C * 2^shift + A, so that one LDS atomic adds both.  Wide: 64 bits, shift 32.
+ * Narrow: 32 bits, shift 23 -- for phases in which no round's events can leave |A| < 2^22 and
+ * |C| < 2^8 (the schedule stage checks it from the parallelism, the largest prompt and the
+ * slice); the window then holds twice the rounds and its atomics are half as wide.  Whatever the
+ * order of the additions, the final sums decode exactly while they are in range.
+ */
+template <bool NARROW> struct WinFmt;
+template <> struct WinFmt<false> {
+    typedef unsigned long long T;
+    static __device__ __forceinline__ T starts(uint32_t cnt, int32_t a)
+    {
+        return ((T)cnt << 32) + (T)(long long)a;
+    }
+    static __device__ __forceinline__ T end(int32_t w) { return kEndOne + (T)(long long)(-w); }
+    static __device__ __forceinline__ void decode(T e, int32_t &a, int32_t &c)
+    {
+        a = (int32_t)(uint32_t)e;                        /* signed low word            */
+        c = (int32_t)(uint32_t)(e >> 32) - (a >> 31);    /* undo the low word's borrow */
+    }
+};
+template <> struct WinFmt<true> {
+    typedef uint32_t T;
+    static constexpr uint32_t kShift = 23;
+    static __device__ __forceinline__ T starts(uint32_t cnt, int32_t a) { return (cnt << kShift) + (uint32_t)a; }
+    static __device__ __forceinline__ T end(int32_t w) { return (0u - (1u << kShift)) + (uint32_t)(-w); }
+    static __device__ __forceinline__ void decode(T e, int32_t &a, int32_t &c)
+    {
+        a = (int32_t)(e << (32u - kShift)) >> (32u - kShift); /* the low 23 bits, signed */
+        c = ((int32_t)e - a) >> kShift;                       /* exact: a multiple of 2^23 is left */
+    }
+};
+
+/*
  * One slab [t_s, t_s + len) of one phase variant, by one wavefront.
  * ev: the wavefront's window of packed (C << 32) + A event sums, one per round of the slab.
  * sumF collects the start offsets of the completing runs that start here.
  */
-template <bool PACKED, int WIN>
+template <bool PACKED, int WIN, bool NARROW>
 __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool sps, uint32_t slab,
                                           const uint32_t *buf, uint32_t n_cap, uint32_t s_scalar,
-                                          const EntryFmt &F, unsigned long long *ev, int lane,
+                                          const EntryFmt &F, unsigned long long *window, int lane,
                                           int32_t &pk, unsigned long long &sumF)
 {
+    typedef WinFmt<NARROW> W;
+    typename W::T *const ev = reinterpret_cast<typename W::T *>(window); /* WIN wide or 2 WIN narrow entries */
     const uint32_t t_s = slab * sc.S;
     const uint32_t len = (sc.H - t_s < sc.S) ? (sc.H - t_s) : sc.S;
-    const int per = (int)((len + 63u) >> 6); /* window entries per lane, at most WIN / 64 */
+    const int per = (int)((len + 63u) >> 6); /* window entries per lane */
 
     for (int j = 0; j < per; j++)
-        ev[j * 64 + lane] = 0ull;
+        ev[j * 64 + lane] = 0;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
@@ -172,7 +210,7 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
             A0 += w;
             C0 += 1;
             if (en < (int32_t)len) {
-                atomicAdd(&ev[en], kEndOne + (unsigned long long)(long long)(-w));
+                atomicAdd(&ev[en], W::end(w));
                 touched = true;
             }
         }
@@ -211,8 +249,7 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
             get_entry<PACKED>(buf, n_cap, sl.off + rb + j, d, done, s, s_scalar, F, sl.tau);
             const uint32_t st = f - t_s; /* in [0, len) */
             if (st != cur && accN) {
-                atomicAdd(&ev[cur], ((unsigned long long)accN << 32) +
-                                        (unsigned long long)(long long)(int32_t)(accS - __umul24(accN, cur)));
+                atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
                 accS = 0;
                 accN = 0;
             }
@@ -221,7 +258,7 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
             accN += 1u;
             const uint32_t en = st + d;
             if (en < len)
-                atomicAdd(&ev[en], kEndOne + (unsigned long long)(long long)(int32_t)(st - (s + 1u)));
+                atomicAdd(&ev[en], W::end((int32_t)((s + 1u) - st)));
             if (F.all_done) {
                 sum_st += st;
             } else {
@@ -236,8 +273,7 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
         if (F.all_done)
             n_done = cnt;
         if (accN)
-            atomicAdd(&ev[cur], ((unsigned long long)accN << 32) +
-                                    (unsigned long long)(long long)(int32_t)(accS - __umul24(accN, cur)));
+            atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
     }
     sumF += (unsigned long long)sum_st + (unsigned long long)n_done * (unsigned long long)t_s;
     if (r0 < r1) { /* the same for every lane */
@@ -253,14 +289,13 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
-    constexpr int kPer = WIN / 64; /* window entries per lane, at most */
+    constexpr int kPer = (NARROW ? 2 * WIN : WIN) / 64; /* window entries per lane, at most */
     int32_t la[kPer], lc[kPer];
     int32_t sa = 0, sc_ = 0;
 #pragma unroll
     for (int j = 0; j < kPer; j++) {
-        const unsigned long long e = (j < per) ? ev[lane * per + j] : 0ull;
-        la[j] = (int32_t)(uint32_t)e;                        /* A, signed low word          */
-        lc[j] = (int32_t)(uint32_t)(e >> 32) - (la[j] >> 31); /* C: undo the low word's borrow */
+        const typename W::T e = (j < per) ? ev[lane * per + j] : (typename W::T)0;
+        W::decode(e, la[j], lc[j]);
         sa += la[j];
         sc_ += lc[j];
     }
@@ -272,7 +307,7 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
             A += la[j];
             C += lc[j];
             const int32_t t = lane * per + j;
-            const int32_t occ = A + __mul24(t, C); /* t < 2^9, |C| < 2^23 by the range check */
+            const int32_t occ = A + __mul24(t, C); /* t < 2^10, |C| < 2^22 by the range check */
             if ((uint32_t)t < len && occ > pk)
                 pk = occ;
         }

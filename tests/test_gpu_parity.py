@@ -246,6 +246,29 @@ def test_long_thin_phases_are_evaluated_run_by_run(K):
     assert_same(got, want, ("peak", "feasible", "flow", "job_steps", "n_completed"))
 
 
+def test_window_formats_at_their_boundary(K):
+    # A phase whose per-round event sums are guaranteed to fit 23 + 9 signed bits is evaluated in 32-bit
+    # windows, any other in 64-bit ones; the guarantee is 2 min(n, k) (s_max + tau + 513) < 2^22 and
+    # min(n, k) < 256.  Instances on either side of both limits, with as many runs starting and ending
+    # in one round as the parallelism allows and prompts as large as the limit lets them be.
+    rng = np.random.default_rng(23)
+    n = 700
+    for k, smax in [(255, 7702), (255, 7703), (256, 3000), (255, 100), (200, 9000), (200, 9960), (200, 9970)]:
+        o = np.full((3, n), 7, np.int32)
+        o[1] = rng.integers(1, 9, n)                      # ragged ends inside the slice of 8
+        o[2, ::2] = 8
+        s = np.full((3, n), smax, np.int32)
+        s[2] = rng.integers(0, smax + 1, n)
+        s[2, 0] = smax
+        M = 10 ** 9                                       # the forced parallelism decides, not the budget
+        pts = [(8, 1, k, 0), (8, 0, k, 0), (1, 0, k, 1), (2, 1, k, 1)]
+        assert_same(run_gba(K, o, s, M, pts), O.gba_simulate_batch(o, s, M, pts))
+        tau = [8, 8, 7, 16]
+        got = host(K.schedule_eval(dev(o), dev(s), M, tau, [k] * 4, [0, 1, 1, 0]))
+        want = O.schedule_eval_batch(o, s, M, list(zip(tau, [k] * 4, [0, 1, 1, 0])))
+        assert_same(got, want, ("peak", "feasible", "flow", "job_steps", "n_completed"))
+
+
 def test_degenerate_inputs(K):
     # all jobs identical and of length one; one job; budget that admits one job at a time
     o = np.ones((3, 130), np.int32)
