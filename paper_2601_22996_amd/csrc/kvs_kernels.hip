@@ -77,9 +77,6 @@ constexpr int MODE_GBA = 0, MODE_GSA = 1, MODE_SINGLE = 2;
  *           leave behind because a value is too wide for their one-word entries.
  * The first four read the jobs from memory once (STREAM: once per batch of phases).
  */
-#ifndef KVS_DEEP
-#define KVS_DEEP 4
-#endif
 constexpr int KIND_NESTED = 0, KIND_ALIVE = 1, KIND_GATHER = 2, KIND_STREAM = 3, KIND_WIDE = 4;
 
 struct JobsDev {
@@ -363,7 +360,7 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
             /* The loads of kDeep chunks are issued before the first is looked at: a segment is
              * only a few chunks long, and a workgroup in this pass has nothing else to wait with
              * (the registers are free: the evaluation's are not live yet). */
-            constexpr uint32_t kDeep = KVS_DEEP;
+            constexpr uint32_t kDeep = 4;
             for (uint32_t base = seg_lo; base < seg_hi; base += 256u * kDeep) {
                 Quad q[kDeep];
 #pragma unroll
