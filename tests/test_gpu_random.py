@@ -114,6 +114,38 @@ def sweep_case(K, seed):
                 label + f" ladders={[l.tolist() for l in lads]} pts={pts}")
 
 
+def refill_case(K, seed):
+    # Algorithm 2 with dynamic refill: sizes whose baseline schedule fits LDS (tight budgets make it long)
+    rng = np.random.default_rng(seed)
+    n = int(rng.choice([1, 2, 5, 63, 64, 65, 200, 511, 1000, 1600]))
+    I = int(rng.integers(1, 5))
+    omax = int(rng.choice([1, 3, 30, 250]))
+    o = rng.integers(1, omax + 1, (I, n)).astype(np.int32) if rng.integers(0, 2) else \
+        np.minimum(rng.geometric(1.0 / max(1.5, omax / 4), (I, n)), omax).astype(np.int32)
+    smax = int(rng.choice([0, 7, 300]))
+    s = rng.integers(0, smax + 1, (I, n)).astype(np.int32) if rng.integers(0, 2) else int(rng.integers(0, smax + 1))
+    M = int(omax + smax + rng.choice([0, 3, 50]) + (smax + omax) * max(1, n // 25) * int(rng.choice([1, 1, 4])))
+    pts = [(int(rng.choice([1, 2, 3, 8, 64])), int(rng.integers(0, 2)), int(rng.choice([0, 0, 0, max(2, n // 10), 100000])),
+            K.MODE_GBAD) for _ in range(int(rng.integers(1, 6)))]
+    label = f"seed {seed}: refill n={n} I={I} omax={omax} smax={smax} M={M} pts={pts}"
+    got = K.gba_simulate(dev(o), s if np.isscalar(s) else dev(s), M, pts)
+    torch.cuda.synchronize()
+    want = O.gbad_simulate_batch(o, s, M, [p[:3] for p in pts])
+    # a baseline too long for LDS is reported in-band; everything else must agree
+    f = got["feasible"].cpu().numpy()
+    keep = f != K.FEASIBLE_ERANGE
+    assert keep.mean() > 0.5 or n >= 1000, label + ": most evaluations out of range"
+    for key in KEYS:
+        g, w = got[key].cpu().numpy(), want[key]
+        assert np.array_equal(g[keep], w[keep]), label + f": {key} differs"
+
+
+@pytest.mark.parametrize("block", range(2))
+def test_random_refill(K, block):
+    for seed in range(11000 + 60 * block, 11000 + 60 * (block + 1)):
+        refill_case(K, seed)
+
+
 @pytest.mark.parametrize("block", range(6))
 def test_random_sweeps(K, block):
     for seed in range(7000 + 100 * block, 7000 + 100 * (block + 1)):
