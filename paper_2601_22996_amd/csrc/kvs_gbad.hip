@@ -46,8 +46,8 @@ struct DJobs {
     int32_t n_inst, n_jobs;
     uint32_t s_scalar;
     uint32_t cap; /* rounds of the schedule that fit LDS beside the jobs */
-    uint32_t tier; /* 0: an evaluation that needs more rounds is left to the next launch; 1: that launch,
-                      which takes only those; 2: the only launch                                        */
+    uint32_t only_marked; /* take only the evaluations the launch before left behind            */
+    uint32_t may_defer;   /* an evaluation that needs more rounds is left to the next launch */
     uint64_t M;
 };
 
@@ -88,8 +88,8 @@ __global__ __launch_bounds__(64) void kvs_gbad_kernel(DJobs J, DPoints P, int64_
 
     const int lane = threadIdx.x;
     const uint32_t inst = blockIdx.x, pt = blockIdx.y;
-    if (J.tier == 1 && feasible[(size_t)P.q[pt] * (size_t)J.n_inst + inst] != FEASIBLE_PENDING)
-        return; /* done by the launch before */
+    if (J.only_marked && feasible[(size_t)P.q[pt] * (size_t)J.n_inst + inst] != FEASIBLE_PENDING)
+        return; /* done by a launch before */
     const uint32_t n = (uint32_t)J.n_jobs;
     const size_t row = (size_t)inst * n;
     uint32_t *const ordO = lds, *const ordS = lds + n;
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(64) void kvs_gbad_kernel(DJobs J, DPoints P, int64_
             if (err)
                 f |= 8u; /* this evaluation leaves the range in some class */
             else if (total > (unsigned long long)J.cap)
-                f |= (J.tier == 0 && f == 0) ? 16u : 8u; /* more rounds than fit: the next launch has more room, or none has */
+                f |= (J.may_defer && f == 0) ? 16u : 8u; /* more rounds than fit: the next launch has more room, or none has */
             flags = f;
             horizon = (uint32_t)(total > (unsigned long long)J.cap ? 0ull : total);
         }
@@ -378,16 +378,16 @@ int32_t kvs_gbad_run(const kvs_jobs_t *jobs, const kvs_point_t *pts, const int32
     J.n_jobs = jobs->n_jobs;
     J.s_scalar = jobs->s ? 0u : (uint32_t)jobs->s_scalar;
     J.M = (uint64_t)jobs->M;
-    /* Two launches.  The first gives an evaluation a third of a compute unit's LDS (the jobs, two
-     * words each, and the rounds that fit beside them: about 10 000 rounds for 1 000 jobs), so that
-     * three share a compute unit -- an evaluation is one wavefront working through dependent LDS
-     * operations, and only company hides that; an evaluation whose baseline lasts longer marks
-     * itself, and the second launch, with all the LDS of a compute unit for one evaluation, takes
-     * only those.  Instances too large for the first go straight to the second. */
-    const size_t room = (kLdsPerGroup - (size_t)fixed) & ~(size_t)15;
-    const size_t small = ((kLdsPerGroup / 3) - (size_t)fixed - 64) & ~(size_t)15;
+    /* Up to three launches.  An evaluation is one wavefront working through dependent LDS
+     * operations, and only company on its compute unit hides that; what limits the company is
+     * the LDS an evaluation is given (the jobs, two words each, and one word per round of the
+     * baseline schedule).  So the first launch gives every evaluation a quarter of a compute
+     * unit's LDS, an evaluation whose baseline lasts longer marks itself, the second launch
+     * takes only those with half of the LDS each, the third the rest with all of it.  Sizes at
+     * which the jobs leave too little room for rounds are skipped. */
+    const size_t whole = (kLdsPerGroup - (size_t)fixed) & ~(size_t)15;
     const size_t for_jobs = sizeof(uint32_t) * 2u * (size_t)jobs->n_jobs;
-    if (for_jobs + 4096 > room)
+    if (for_jobs + 4096 > whole)
         return KVS_ELIMIT;
     DPoints P;
     P.n = n_pts;
@@ -398,21 +398,25 @@ int32_t kvs_gbad_run(const kvs_jobs_t *jobs, const kvs_point_t *pts, const int32
         P.q[j] = (uint16_t)rows[j];
     }
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kvs_gbad_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)room) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)whole) != hipSuccess)
         return KVS_EHIP;
     const dim3 grid((uint32_t)jobs->n_instances, (uint32_t)n_pts);
-    const bool two = for_jobs + 8192 <= small;
-    if (two) {
-        J.cap = (uint32_t)((small - for_jobs) / sizeof(int32_t));
-        J.tier = 0;
-        hipLaunchKernelGGL(kvs_gbad_kernel, grid, dim3(64), small, static_cast<hipStream_t>(stream), J, P, peak,
+    size_t sizes[3];
+    int n_sizes = 0;
+    for (size_t parts = 4; parts >= 2; parts /= 2) {
+        const size_t room = ((kLdsPerGroup / parts) - (size_t)fixed - 64) & ~(size_t)15;
+        if (for_jobs + 8192 <= room)
+            sizes[n_sizes++] = room;
+    }
+    sizes[n_sizes++] = whole;
+    for (int i = 0; i < n_sizes; i++) {
+        J.cap = (uint32_t)((sizes[i] - for_jobs) / sizeof(int32_t));
+        J.only_marked = i > 0 ? 1u : 0u;
+        J.may_defer = i + 1 < n_sizes ? 1u : 0u;
+        hipLaunchKernelGGL(kvs_gbad_kernel, grid, dim3(64), sizes[i], static_cast<hipStream_t>(stream), J, P, peak,
                            feasible, flow, job_steps);
         if (hipGetLastError() != hipSuccess)
             return KVS_EHIP;
     }
-    J.cap = (uint32_t)((room - for_jobs) / sizeof(int32_t));
-    J.tier = two ? 1u : 2u;
-    hipLaunchKernelGGL(kvs_gbad_kernel, grid, dim3(64), room, static_cast<hipStream_t>(stream), J, P, peak, feasible,
-                       flow, job_steps);
-    return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
+    return KVS_OK;
 }
