@@ -503,7 +503,8 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
         F.all_done = false;
         const uint32_t sbits = F.has_s ? 32u - kvs_clz32(maxS_sh) : 0u;
         F.swidth = sbits;
-        const bool fits = F.dbits + 1u + sbits <= 32u;
+        /* the prompt field is read with one shift, so it starts below bit 32 even when it is empty */
+        const bool fits = F.dbits + 1u + sbits <= 32u && F.sshift <= 31u;
         if (PACKED && !fits && flags == 0) {
             if (tid < G.n_pts)
                 out.feasible[(size_t)G.pt_q[tid] * (size_t)J.n_inst + inst] = FEASIBLE_PENDING;

@@ -123,7 +123,7 @@ __device__ __forceinline__ void get_entry(const uint32_t *buf, uint32_t n_cap, u
         } else {
             done = F.all_done || ((w >> F.dbits) & 1u);
         }
-        s = __builtin_amdgcn_ubfe(w, F.sshift, F.swidth) + F.s_add; /* width 0 extracts 0 */
+        s = (w >> F.sshift) + F.s_add; /* the prompt is the topmost field; nothing above sshift <= 31 when none is stored */
     } else {
         d = w & 0x7fffffffu;
         done = w >> 31;
@@ -224,58 +224,84 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
     {
         const uint32_t blk = ((r2 - r1 + 63u) >> 6) | 1u;
         const uint32_t rb = r1 + (uint32_t)lane * blk;
-        /* inside a block the start offset is carried from rank to rank (quotient and
-         * remainder of r tau / k, or of r / k) instead of divided out each time */
-        uint32_t f = 0, rem = 0;
-        if (rb < r2) {
-            if (sps) {
+        const uint32_t cnt = rb < r2 ? (r2 - rb < blk ? r2 - rb : blk) : 0u;
+        if (sps) {
+            /* inside a block the start offset is carried from rank to rank (quotient and
+             * remainder of r tau / k) instead of divided out each time: per rank the remainder
+             * grows by tau mod k, and the offset by floor(tau / k) and one more when it wraps */
+            uint32_t f = 0, rem = 0;
+            if (cnt) {
                 f = kvs_div(rb * sl.tau, sc.div);
                 rem = rb * sl.tau - f * sc.k;
-            } else {
-                const uint32_t b = kvs_div(rb, sc.div);
-                f = b * sl.tau;
-                rem = rb - b * sc.k;
             }
-        }
-        /* per rank: SPS adds tau to the remainder modulo k, SimS adds 1 modulo k (tau rounds per wrap) */
-        const uint32_t q_step = sps ? kvs_div(sl.tau, sc.div) : 0u;
-        const uint32_t r_step = sps ? sl.tau - q_step * sc.k : 1u;
-        const uint32_t wrap = sps ? 1u : sl.tau;
-        uint32_t cur = 0, accS = 0, accN = 0;
-        const uint32_t cnt = rb < r2 ? (r2 - rb < blk ? r2 - rb : blk) : 0u;
-        for (uint32_t j = 0; j < cnt; j++) {
-            uint32_t d, s;
-            bool done;
-            get_entry<PACKED>(buf, n_cap, sl.off + rb + j, d, done, s, s_scalar, F, sl.tau);
-            const uint32_t st = f - t_s; /* in [0, len) */
-            if (st != cur && accN) {
+            const uint32_t q_step = kvs_div(sl.tau, sc.div);
+            const uint32_t r_step = sl.tau - q_step * sc.k;
+            uint32_t cur = f - t_s, accS = 0, accN = 0;
+            for (uint32_t j = 0; j < cnt; j++) {
+                uint32_t d, s;
+                bool done;
+                get_entry<PACKED>(buf, n_cap, sl.off + rb + j, d, done, s, s_scalar, F, sl.tau);
+                const uint32_t st = f - t_s; /* in [0, len) */
+                if (st != cur) { /* cur is the round of the run before: something is held */
+                    atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
+                    accS = 0;
+                    accN = 0;
+                }
+                cur = st;
+                accS += s + 1u;
+                accN += 1u;
+                const uint32_t en = st + d;
+                if (en < len)
+                    atomicAdd(&ev[en], W::end((int32_t)((s + 1u) - st)));
+                if (!F.all_done) {
+                    sum_st += done ? st : 0u;
+                    n_done += done ? 1u : 0u;
+                }
+                rem += r_step;
+                const bool over = rem >= sc.k;
+                rem -= over ? sc.k : 0u;
+                f += q_step + (over ? 1u : 0u);
+            }
+            if (accN)
                 atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
-                accS = 0;
-                accN = 0;
+        } else {
+            /* SimS: the runs of a batch start together, so a block is gone through batch by
+             * batch with the round fixed, and each stretch adds its start events once */
+            uint32_t left = cnt, pos = sl.off + rb, inb = 0, st = 0;
+            if (cnt) {
+                const uint32_t b = kvs_div(rb, sc.div);
+                inb = rb - b * sc.k;       /* place of the first rank in its batch */
+                st = b * sl.tau - t_s;     /* in [0, len) */
             }
-            cur = st;
-            accS += s + 1u;
-            accN += 1u;
-            const uint32_t en = st + d;
-            if (en < len)
-                atomicAdd(&ev[en], W::end((int32_t)((s + 1u) - st)));
-            if (F.all_done) {
-                sum_st += st;
-            } else {
-                sum_st += done ? st : 0u;
-                n_done += done ? 1u : 0u;
+            while (left) {
+                uint32_t seg = sc.k - inb;
+                seg = seg < left ? seg : left;
+                uint32_t accS = 0, seg_done = 0;
+                for (uint32_t j = 0; j < seg; j++) {
+                    uint32_t d, s;
+                    bool done;
+                    get_entry<PACKED>(buf, n_cap, pos + j, d, done, s, s_scalar, F, sl.tau);
+                    accS += s + 1u;
+                    const uint32_t en = st + d;
+                    if (en < len)
+                        atomicAdd(&ev[en], W::end((int32_t)((s + 1u) - st)));
+                    if (!F.all_done)
+                        seg_done += done ? 1u : 0u;
+                }
+                atomicAdd(&ev[st], W::starts(seg, (int32_t)(accS - __umul24(seg, st))));
+                if (!F.all_done) {
+                    sum_st += __umul24(seg_done, st);
+                    n_done += seg_done;
+                }
+                pos += seg;
+                left -= seg;
+                inb = 0;
+                st += sl.tau;
             }
-            rem += r_step;
-            const bool over = rem >= sc.k;
-            rem -= over ? sc.k : 0u;
-            f += q_step + (over ? wrap : 0u);
         }
-        if (F.all_done)
-            n_done = cnt;
-        if (accN)
-            atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
     }
-    sumF += (unsigned long long)sum_st + (unsigned long long)n_done * (unsigned long long)t_s;
+    if (!F.all_done) /* else the caller has the sum in closed form */
+        sumF += (unsigned long long)sum_st + (unsigned long long)n_done * (unsigned long long)t_s;
     if (r0 < r1) { /* the same for every lane */
         A0 = wave_sum(A0);
         C0 = wave_sum(C0);
