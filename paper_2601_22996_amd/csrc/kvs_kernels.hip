@@ -626,6 +626,12 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
              * slabs repeat less work at their edges, and that outweighs the balance);
              * SimS batches do not overlap, so whole batches per slab need no carry-in */
             uint32_t S = ((2 * sc.H + NW - 1) / NW + 63u) & ~63u;
+            if (sps) { /* ... but long enough for about 1024 runs to start inside one: the work at
+                          a slab's edges (window, carry-in, scan) is then small beside its runs */
+                uint64_t need = kvs_udiv(1024u * tau, k);
+                need = need > wcap ? wcap : need;
+                S = S < (uint32_t)need ? (((uint32_t)need + 63u) & ~63u) : S;
+            }
             S = S > wcap ? wcap : S;
             if (!sps && sl.tau <= wcap) {
                 uint32_t b = S / sl.tau;
@@ -871,12 +877,19 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
         const uint32_t hi = lo + span < cnt ? lo + span : cnt;
         uint32_t held[kHold];
         uint32_t kept = 0;
+        /* all the reads first, none of them under a branch, so that they are in flight together
+         * (an index past the stretch reads the stretch's last word, which is then ignored) */
+        const uint32_t last = hi ? hi - 1u : 0u;
+#pragma unroll
+        for (int c = 0; c < kHold; c++) {
+            const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
+            held[c] = buf[idx < last ? idx : last];
+        }
 #pragma unroll
         for (int c = 0; c < kHold; c++) {
             if (lo + (uint32_t)c * 64u >= hi)
                 break; /* the rest of the stretch is empty (the same for all lanes) */
             const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
-            held[c] = (idx < hi) ? buf[idx] : 0xffffffffu;
             const bool keep = idx < hi && ((held[c] & dmask) <= theta) != long_first;
             kept += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(keep));
         }
