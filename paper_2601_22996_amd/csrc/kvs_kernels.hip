@@ -226,6 +226,9 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
     __shared__ uint32_t cumE[NW][kLevels]; /* per wavefront: jobs of its segment entering at levels <= l */
     __shared__ uint32_t cumL[NW][kLevels]; /* ... leaving at levels <= l                                  */
     __shared__ uint32_t totE[kLevels], totL[kLevels];
+    __shared__ uint32_t upE[kLevels], upL[kLevels], upS[kLevels]; /* over the levels up to l: sums of totE, of totL, largest sMaxEnter */
+    __shared__ uint8_t used[kSlots]; /* the slots that have a schedule of their own */
+    __shared__ uint32_t n_used;
     __shared__ uint32_t sMaxPart[kLevels], sMaxEnter[kLevels];
     __shared__ uint32_t lad[kLevels]; /* slice of every level, saturated at 2^32 - 1 */
     __shared__ Slot slot[kSlots];
@@ -459,10 +462,29 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
         }
         totE[tid] = e;
         totL[tid] = l;
+        /* the levels sit in the first lanes of the first wavefront: running sums and maximum */
+        static_assert(kLevels <= 64, "one lane per level");
+        uint32_t ue = e, ul = l, us = sMaxEnter[tid];
+#pragma unroll
+        for (int off = 1; off < kLevels; off <<= 1) {
+            const uint32_t a = __shfl_up(ue, off), b = __shfl_up(ul, off), c = __shfl_up(us, off);
+            if (tid >= off) {
+                ue += a;
+                ul += b;
+                us = c > us ? c : us;
+            }
+        }
+        upE[tid] = ue;
+        upL[tid] = ul;
+        upS[tid] = us;
         if (ALIVE && per_job_s) { /* a level's phase holds the jobs that complete there or later */
-            uint32_t m = 0;
-            for (int g = tid; g < kLevels; g++)
-                m = sMaxEnter[g] > m ? sMaxEnter[g] : m;
+            uint32_t m = sMaxEnter[tid];
+#pragma unroll
+            for (int off = 1; off < kLevels; off <<= 1) {
+                const uint32_t c = __shfl_down(m, off);
+                if (tid + off < kLevels)
+                    m = c > m ? c : m;
+            }
             sMaxPart[tid] = m;
         }
     }
@@ -531,32 +553,19 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
             lv = (uint32_t)tid;
             used = (mode != MODE_SINGLE) && (lv > m_min);
             if (used) {
-                uint32_t enter = 0, left = 0, off = 0;
-                for (uint32_t l = 0; l <= lv; l++)
-                    enter += totE[l];
-                for (uint32_t l = 0; l < lv; l++)
-                    left += totL[l];
+                const uint32_t enter = upE[lv], left = lv ? upL[lv - 1u] : 0u;
                 sl.n = enter - left;
                 sl.done = totL[lv];
                 if (per_job_s)
                     sl.smax = NESTED ? sMaxEnter[lv] : sMaxPart[lv];
-                if (one_phase_each) { /* the multisplit keeps every level's jobs side by side */
-                    for (uint32_t l = 0; l < lv; l++)
-                        off += totE[l];
-                    sl.off = off;
-                }
+                if (one_phase_each) /* the multisplit keeps every level's jobs side by side */
+                    sl.off = lv ? upE[lv - 1u] : 0u;
             }
         } else if (tid - kLevels < (int)G.n_m) {
             lv = G.m[tid - kLevels];
             used = true;
-            uint32_t enter = 0, done = 0, below = 0, sm = 0;
-            for (uint32_t l = 0; l <= lv; l++) {
-                enter += totE[l];
-                done += totL[l];
-                sm = sMaxEnter[l] > sm ? sMaxEnter[l] : sm;
-                if (l < lv)
-                    below += totL[l]; /* jobs that are through before level lv */
-            }
+            const uint32_t enter = upE[lv], done = upL[lv], sm = upS[lv];
+            const uint32_t below = lv ? upL[lv - 1u] : 0u; /* jobs that are through before level lv */
             sl.n = enter;
             sl.done = done;
             if (per_job_s)
@@ -584,9 +593,44 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
     }
     __syncthreads();
 
-    /* ---- the schedule of every (variant, slot) ---- */
-    for (int i = tid; i < (int)G.n_v * kSlots; i += T) {
+    /* The slots that get schedules of their own (somebody takes part, and no other slot holds
+     * the same phase), listed side by side: working out a schedule is a long serial piece of
+     * code, and a wavefront pays for it in full however few of its lanes have one to do. */
+    if (wave == 0) {
+        uint32_t cu = 0;
+        for (int base = 0; base < kSlots; base += 64) {
+            const int si = base + lane;
+            const bool u = si < kSlots && slot[si].n > 0 && slot[si].alias == (uint32_t)si;
+            const uint64_t mk = __ballot(u);
+            if (u)
+                used[cu + lanes_below(mk)] = (uint8_t)si;
+            cu += (uint32_t)__popcll(mk);
+        }
+        if (lane == 0)
+            n_used = cu;
+    }
+    for (int i = tid; i < (int)G.n_v * kSlots; i += T) { /* the others: nothing to evaluate */
         const int vi = i / kSlots, si = i % kSlots;
+        if (slot[si].n > 0 && slot[si].alias == (uint32_t)si)
+            continue;
+        Sched sc;
+        sc.k = 1;
+        sc.H = 0;
+        sc.S = 64;
+        sc.nslab = 0;
+        sc.bad = 0;
+        sc.narrow = 0;
+        sc.div = kvs_make_divisor(1);
+        sched[vi][si] = sc;
+        res[vi][si].peak = 0;
+        res[vi][si].sumF = 0;
+    }
+    __syncthreads();
+
+    /* ---- the schedule of every (variant, slot) ---- */
+    const int n_sched = (int)G.n_v * (int)n_used;
+    for (int i = tid; i < n_sched; i += T) {
+        const int vi = i / (int)n_used, si = used[i % (int)n_used];
         const Slot sl = slot[si];
         const bool sps = (G.v_sched[vi] == KVS_SCHED_SPS);
         Sched sc;
