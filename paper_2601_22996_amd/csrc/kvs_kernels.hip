@@ -1045,7 +1045,8 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                     break;
                 alive -= totL[si];
                 if (left < cnt) {
-                    __syncthreads(); /* the phases evaluated so far have read the list */
+                    /* no barrier here: the partition first only reads the list, as the phases
+                     * evaluated so far do, and has a barrier of its own before it writes */
                     split_front(cnt, lad[si - 1], true);
                     cnt = left;
                 }
@@ -1131,10 +1132,11 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                 /* buf[0 .. cnt) holds the jobs of the levels 0 .. g in input order */
                 if (mi >= 0 && G.m[mi] == g) {
                     const int si = kLevels + mi;
-                    if (slot[si].n > 0 && slot[si].alias == (uint32_t)si) {
+                    /* no barrier after it: whatever follows only reads the buffer until the
+                     * barrier inside the next partition, which every wavefront reaches after its
+                     * share of this phase */
+                    if (slot[si].n > 0 && slot[si].alias == (uint32_t)si)
                         eval_slot(si);
-                        __syncthreads();
-                    }
                     mi--;
                 }
                 if (g == m_min)
