@@ -28,6 +28,7 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <initializer_list>
 
 #include "kvs_internal.h"
 #include "kvs_math.h"
@@ -266,70 +267,100 @@ __global__ __launch_bounds__(64) void kvs_gbad_kernel(DJobs J, DPoints P, int64_
     __syncthreads();
 
     /* a run of o rounds from round t, first round s1: added to (sign = 1) or taken out of the rounds */
+    /* (additions carried out by the LDS unit itself, in the order they are issued: nothing comes
+     * back, so the wavefront does not wait for one round's old value before it goes on) */
     auto ramp = [&](uint32_t t, uint32_t o, uint32_t s1, int32_t sign) {
         for (uint32_t u = (uint32_t)lane; u < o; u += 64)
-            occ[t + u] += sign * (int32_t)(s1 + u);
+            atomicAdd(&occ[t + u], sign * (int32_t)(s1 + u));
     };
-    /* baseline start of the r-th job of class c */
-    auto base_of = [&](uint32_t c, uint32_t r) {
-        const uint32_t f = sps ? kvs_div(r * tauc[c], divc[c]) : kvs_div(r, divc[c]) * tauc[c];
-        return beginc[c] + f;
+    /* The jobs are gone through in the baseline's order.  64 of them at a time sit in the lanes
+     * (lane j: job pos0 + j) and are handed to the whole wavefront one after the other, and the
+     * current class's slice, divisor and first round are kept in registers: per job nothing is
+     * fetched from LDS but the rounds themselves. */
+    uint32_t cls = 0, cls_r = 0;           /* class of the next job, and its place in the class */
+    uint32_t cls_n = 0, cls_tau = 0, cls_begin = 0;
+    kvs_divisor_t cls_div = kvs_make_divisor(1);
+    auto load_class = [&]() {
+        cls_n = cnt[cls];
+        cls_tau = tauc[cls];
+        cls_begin = beginc[cls];
+        cls_div = divc[cls];
+    };
+    auto next_base = [&]() { /* baseline start of the next job; moves on to it */
+        while (cls_r >= cls_n) { /* next class with a job */
+            cls++;
+            cls_r = 0;
+            load_class();
+        }
+        const uint32_t f = sps ? kvs_div(cls_r * cls_tau, cls_div) : kvs_div(cls_r, cls_div) * cls_tau;
+        cls_r++;
+        return cls_begin + f;
     };
 
     /* ---- everybody at the baseline start ---- */
-    {
-        uint32_t c = 0, r = 0;
-        for (uint32_t pos = 0; pos < n; pos++) {
-            while (r >= cnt[c]) { /* next class with a job */
-                c++;
-                r = 0;
-            }
-            ramp(base_of(c, r), ordO[pos], ordS[pos], 1);
-            r++;
-        }
+    load_class();
+    for (uint32_t pos0 = 0; pos0 < n; pos0 += 64) {
+        const uint32_t mine = pos0 + (uint32_t)lane < n ? pos0 + (uint32_t)lane : n - 1u;
+        const uint32_t myO = ordO[mine], myS = ordS[mine];
+        const uint32_t m = n - pos0 < 64u ? n - pos0 : 64u;
+        for (uint32_t j = 0; j < m; j++)
+            ramp(next_base(), __builtin_amdgcn_readlane(myO, (int)j), __builtin_amdgcn_readlane(myS, (int)j), 1);
     }
     __syncthreads();
 
     /* ---- refill, one job after the other ---- */
     unsigned long long fsum = 0;
+    const uint32_t m32 = J.M > 0xffffffffull ? 0xffffffffu : (uint32_t)J.M; /* a round holds less than 2^32 */
     {
-        uint32_t c = 0, r = 0, prev = 0;
-        for (uint32_t pos = 0; pos < n; pos++) {
-            while (r >= cnt[c]) {
-                c++;
-                r = 0;
-            }
-            const uint32_t o = ordO[pos], s1 = ordS[pos];
-            const uint32_t base = base_of(c, r);
-            r++;
+        uint32_t prev = 0;
+        cls = 0;
+        cls_r = 0;
+        load_class();
+        for (uint32_t pos0 = 0; pos0 < n; pos0 += 64) {
+          const uint32_t mine = pos0 + (uint32_t)lane < n ? pos0 + (uint32_t)lane : n - 1u;
+          const uint32_t myO = ordO[mine], myS = ordS[mine];
+          const uint32_t m = n - pos0 < 64u ? n - pos0 : 64u;
+          for (uint32_t j = 0; j < m; j++) {
+            const uint32_t o = __builtin_amdgcn_readlane(myO, (int)j), s1 = __builtin_amdgcn_readlane(myS, (int)j);
+            const uint32_t base = next_base();
             uint32_t t = prev;
             while (t < base) {
-                /* the first 64 rounds of the run that hold a round over the budget decide how far
-                 * the start has to move: past that round, or far enough to be that much smaller
-                 * in it, whichever comes first; the largest such move over those rounds skips
-                 * only starts that fail in one of them */
-                uint32_t next = 0;
-                for (uint32_t u0 = 0; u0 < o && next == 0; u0 += 64) {
-                    const uint32_t u = u0 + (uint32_t)lane;
-                    uint32_t cand = 0;
-                    if (u < o) {
-                        /* what the others hold in that round: the job's own run, still at its baseline
-                         * start, is taken off */
-                        const uint32_t x = t + u;
-                        const int64_t own = (x >= base) ? (int64_t)(s1 + (x - base)) : 0; /* x < base + o: t < base */
-                        const int64_t over = (int64_t)occ[x] - own + (int64_t)(s1 + u) - (int64_t)J.M;
-                        if (over > 0)
-                            cand = (over < (int64_t)(u + 1u)) ? t + (uint32_t)over : t + u + 1u;
+                /* every round of the run is looked at, 64 at a time; a round over the budget rules
+                 * out every start up to it, or up to where the run would be that much smaller in
+                 * it, whichever comes first; the largest such move over all failing rounds skips
+                 * only starts that fail in one of them.  The lanes keep their own largest move and
+                 * the wavefront is asked once per start, not once per 64 rounds: most starts fit. */
+                uint32_t cand = 0;
+                auto look = [&](uint32_t u, uint32_t held_all) {
+                    /* what the others hold in that round: the job's own run, still at its baseline
+                     * start, is taken off */
+                    const uint32_t x = t + u;
+                    const uint32_t own = (x >= base) ? s1 + (x - base) : 0u; /* x < base + o: t < base */
+                    const uint32_t held = held_all - own + (s1 + u); /* both parts below 2^31 */
+                    if (held > m32) {
+                        const uint32_t over = held - m32;
+                        const uint32_t c = (over < u + 1u) ? t + over : t + u + 1u;
+                        cand = c > cand ? c : cand;
                     }
-                    next = wave_max_u32(cand);
+                };
+                uint32_t u = (uint32_t)lane;
+                for (; u + 192u < o; u += 256u) { /* four reads in flight */
+                    const uint32_t h0 = (uint32_t)occ[t + u], h1 = (uint32_t)occ[t + u + 64u],
+                                   h2 = (uint32_t)occ[t + u + 128u], h3 = (uint32_t)occ[t + u + 192u];
+                    look(u, h0);
+                    look(u + 64u, h1);
+                    look(u + 128u, h2);
+                    look(u + 192u, h3);
                 }
+                for (; u < o; u += 64u)
+                    look(u, (uint32_t)occ[t + u]);
+                const uint32_t next = __any(cand != 0) ? wave_max_u32(cand) : 0u;
                 if (next == 0)
                     break; /* fits */
                 t = next;
             }
             if (t < base) { /* it moves */
                 ramp(base, o, s1, -1);
-                wave_sync();
                 ramp(t, o, s1, 1);
                 wave_sync();
             } else {
@@ -337,6 +368,7 @@ __global__ __launch_bounds__(64) void kvs_gbad_kernel(DJobs J, DPoints P, int64_
             }
             prev = t;
             fsum += (unsigned long long)t + o;
+          }
         }
     }
 
@@ -401,9 +433,11 @@ int32_t kvs_gbad_run(const kvs_jobs_t *jobs, const kvs_point_t *pts, const int32
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)whole) != hipSuccess)
         return KVS_EHIP;
     const dim3 grid((uint32_t)jobs->n_instances, (uint32_t)n_pts);
-    size_t sizes[3];
+    size_t sizes[8];
     int n_sizes = 0;
-    for (size_t parts = 4; parts >= 2; parts /= 2) {
+    for (size_t parts : {4, 2}) { /* finer steps were measured: each launch has a tail of its own, and they add up to more */
+        if (kLdsPerGroup / parts < (size_t)fixed + 64 + 16)
+            continue;
         const size_t room = ((kLdsPerGroup / parts) - (size_t)fixed - 64) & ~(size_t)15;
         if (for_jobs + 8192 <= room)
             sizes[n_sizes++] = room;
