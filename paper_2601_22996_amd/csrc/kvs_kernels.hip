@@ -234,7 +234,6 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
     __shared__ Slot slot[kSlots];
     __shared__ Sched sched[kMaxV][kSlots];
     __shared__ Result res[kMaxV][kSlots];
-    __shared__ uint32_t wkeep[NW]; /* per wavefront: entries its stretch keeps in a partition */
     __shared__ uint8_t order[kSlots];      /* GATHERS: the slots to evaluate, batch after batch */
     __shared__ uint8_t bstart[kSlots + 1]; /* ... batch b is order[bstart[b] .. bstart[b + 1])  */
     __shared__ uint32_t n_batches;
@@ -261,7 +260,7 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
     uint8_t *const ga_lds = reinterpret_cast<uint8_t *>(buf + 2u * n); /* COPY only */
 
     /* each wavefront owns a contiguous segment of the jobs */
-    const uint32_t seg = ((n + NW - 1) / NW + 255u) & ~255u; /* whole 256-job chunks */
+    const uint32_t seg = ((n + NW - 1) / NW + 63u) & ~63u; /* whole 64-job chunks: at most HOLD of them */
     const uint32_t seg_lo = (uint32_t)wave * seg < n ? (uint32_t)wave * seg : n;
     const uint32_t seg_hi = seg_lo + seg < n ? seg_lo + seg : n;
 
@@ -462,6 +461,20 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
         }
         totE[tid] = e;
         totL[tid] = l;
+        if (NESTED || ALIVE) {
+            /* The partitions in LDS leave every wavefront the entries that came from its own
+             * segment of the input, so what it keeps and where that goes follow from these counts
+             * and nothing has to be counted again.  For that each count gets, beside it, the sum
+             * over the wavefronts before: of cumE in cumL's place where every job has one phase
+             * (the two are equal there), of cumL in cumE's place where everybody enters at once
+             * (cumE is the segment length there). */
+            uint32_t run = 0;
+            for (int w = 0; w < NW; w++) {
+                const uint32_t c = NESTED ? cumE[w][tid] : cumL[w][tid];
+                (NESTED ? cumL : cumE)[w][tid] = run;
+                run += c;
+            }
+        }
         /* the levels sit in the first lanes of the first wavefront: running sums and maximum */
         static_assert(kLevels <= 64, "one lane per level");
         uint32_t ue = e, ul = l, us = sMaxEnter[tid];
@@ -912,48 +925,27 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
     constexpr int kHold = HOLD; /* the launch guarantees n_jobs <= HOLD * T */
     const uint32_t dmask = (F.dbits >= 32u) ? 0xffffffffu : ((1u << F.dbits) - 1u);
 
-    /* Stable partition of buf[0 .. cnt): entries with duration <= theta keep their order at
-     * the front, the others follow, also in order (long_first: the other way round).  Each wavefront takes a stretch, holds it
-     * in registers across the barrier and writes it back to its two destinations. */
-    auto split_front = [&](uint32_t cnt, uint32_t theta, bool long_first = false) {
-        const uint32_t span = ((cnt + NW - 1) / NW + 63u) & ~63u;
-        const uint32_t lo = (uint32_t)wave * span < cnt ? (uint32_t)wave * span : cnt;
-        const uint32_t hi = lo + span < cnt ? lo + span : cnt;
+    /* Stable partition, wavefront by wavefront: this wavefront's entries buf[in_lo .. in_lo + in_len)
+     * with duration <= theta go to buf[front ..) in their order, the others to buf[back ..) in
+     * theirs (long_first: the other way round; !write_back: the others are dropped).  The caller
+     * knows the places from the per-wavefront counts of pass 1.  The entries are held in
+     * registers across the barrier that separates everybody's reads from everybody's writes. */
+    auto split_owned = [&](uint32_t in_lo, uint32_t in_len, uint32_t theta, bool long_first, uint32_t front,
+                           uint32_t back, bool write_back) {
+        const uint32_t hi = in_lo + in_len;
         uint32_t held[kHold];
-        uint32_t kept = 0;
         /* all the reads first, none of them under a branch, so that they are in flight together
          * (an index past the stretch reads the stretch's last word, which is then ignored) */
         const uint32_t last = hi ? hi - 1u : 0u;
 #pragma unroll
         for (int c = 0; c < kHold; c++) {
-            const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
+            const uint32_t idx = in_lo + (uint32_t)c * 64u + (uint32_t)lane;
             held[c] = buf[idx < last ? idx : last];
         }
-#pragma unroll
-        for (int c = 0; c < kHold; c++) {
-            if (lo + (uint32_t)c * 64u >= hi)
-                break; /* the rest of the stretch is empty (the same for all lanes) */
-            const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
-            const bool keep = idx < hi && ((held[c] & dmask) <= theta) != long_first;
-            kept += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(keep));
-        }
-        if (lane == 0)
-            wkeep[wave] = kept;
         __syncthreads();
-        uint32_t front = 0, back = 0; /* where this wavefront's kept / moved entries begin */
-        for (int w = 0; w < NW; w++) {
-            const uint32_t wlo = (uint32_t)w * span < cnt ? (uint32_t)w * span : cnt;
-            const uint32_t whi = wlo + span < cnt ? wlo + span : cnt;
-            const uint32_t kw = wkeep[w];
-            if (w < wave) {
-                front += kw;
-                back += (whi - wlo) - kw;
-            }
-            back += kw; /* the moved entries start after everything that is kept */
-        }
 #pragma unroll
         for (int c = 0; c < kHold; c++) {
-            const uint32_t at = lo + (uint32_t)c * 64u;
+            const uint32_t at = in_lo + (uint32_t)c * 64u;
             if (at >= hi)
                 break; /* the rest of the stretch is empty (the same for all lanes) */
             /* the entries of a chunk sit in its first lanes, so a lane's rank among them is its
@@ -962,8 +954,10 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
             const bool keep = act && ((held[c] & dmask) <= theta) != long_first;
             const uint64_t bk = __builtin_amdgcn_ballot_w64(keep);
             const uint32_t rk = lanes_below(bk);
-            if (act)
-                buf[keep ? front + rk : back + ((uint32_t)lane - rk)] = held[c];
+            if (keep)
+                buf[front + rk] = held[c];
+            else if (act && write_back)
+                buf[back + ((uint32_t)lane - rk)] = held[c];
             const uint32_t nk = (uint32_t)__popcll(bk);
             const uint32_t na = hi - at < 64u ? hi - at : 64u;
             front += nk;
@@ -972,43 +966,30 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
         __syncthreads();
     };
 
-    /* Stable multisplit by level of buf[b0 .. n) (entries above every merged phase, in input
-     * order) to where the level slots expect them.  cumL serves as per-wavefront histogram. */
-    auto split_tail = [&](uint32_t b0) {
-        const uint32_t cnt = n - b0;
-        const uint32_t span = ((cnt + NW - 1) / NW + 63u) & ~63u;
-        const uint32_t lo = b0 + ((uint32_t)wave * span < cnt ? (uint32_t)wave * span : cnt);
-        const uint32_t hi = (lo + span < n) ? lo + span : n;
-        for (int i = tid; i < NW * kLevels; i += T)
-            (&cumL[0][0])[i] = 0;
-        __syncthreads();
-        uint32_t held[kHold]; /* the levels are worked out twice rather than held as well */
+    /* Stable multisplit by level of this wavefront's entries buf[in_lo .. in_lo + in_len) (levels
+     * above every merged phase, in input order) to where the level slots expect them: a level's
+     * slot takes the wavefronts' shares one after the other.  pre: the sums over the wavefronts
+     * before this one that the totals stage has put beside the counts. */
+    auto split_tail_owned = [&](uint32_t in_lo, uint32_t in_len, const uint32_t *pre) {
+        const uint32_t hi = in_lo + in_len;
+        uint32_t held[kHold];
+        const uint32_t last = hi ? hi - 1u : 0u;
 #pragma unroll
         for (int c = 0; c < kHold; c++) {
-            if (lo + (uint32_t)c * 64u >= hi)
-                break; /* the rest of the stretch is empty (the same for all lanes) */
-            const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
-            held[c] = 0;
-            if (idx < hi) {
-                bool ok = true; /* checked in pass 1 */
-                held[c] = buf[idx];
-                atomicAdd(&cumL[wave][level_of<EXPLICIT>(held[c] & dmask, G, lad, ok)], 1u);
-            }
+            const uint32_t idx = in_lo + (uint32_t)c * 64u + (uint32_t)lane;
+            held[c] = buf[idx < last ? idx : last];
         }
-        __syncthreads();
         uint32_t cur = 0; /* lane l: next free position of level l for this wavefront */
-        if (lane < kLevels) {
-            cur = slot[lane].off;
-            for (int w = 0; w < wave; w++)
-                cur += cumL[w][lane];
-        }
+        if (lane > 0 && lane < kLevels)
+            cur = slot[lane].off + (pre[lane] - pre[lane - 1]);
+        __syncthreads();
 #pragma unroll
         for (int c = 0; c < kHold; c++) {
-            if (lo + (uint32_t)c * 64u >= hi)
+            if (in_lo + (uint32_t)c * 64u >= hi)
                 break; /* the rest of the stretch is empty (the same for all lanes) */
-            const uint32_t idx = lo + (uint32_t)c * 64u + (uint32_t)lane;
+            const uint32_t idx = in_lo + (uint32_t)c * 64u + (uint32_t)lane;
             const bool act = idx < hi;
-            bool ok = true;
+            bool ok = true; /* checked in pass 1 */
             const uint32_t lv = act ? level_of<EXPLICIT>(held[c] & dmask, G, lad, ok) : 0u;
             uint32_t pos = 0;
             uint64_t todo = __ballot(act);
@@ -1039,6 +1020,9 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
             uint32_t alive = n; /* of which are unfinished when the next level begins */
             for (uint32_t l = 0; l <= m_min; l++)
                 alive -= totL[l];
+            /* of this wavefront's segment, and of the segments before it, what has left the list
+             * so far (cumL, and its sums over the wavefronts before in cumE's place) */
+            uint32_t gone_own = 0, gone_before = 0;
             for (int si = (int)m_min + 1; si < kLevels && mode != MODE_SINGLE; si++) {
                 const uint32_t left = alive; /* the jobs longer than the slice below */
                 if (left == 0)
@@ -1047,7 +1031,11 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                 if (left < cnt) {
                     /* no barrier here: the partition first only reads the list, as the phases
                      * evaluated so far do, and has a barrier of its own before it writes */
-                    split_front(cnt, lad[si - 1], true);
+                    const uint32_t out_own = cumL[wave][si - 1], out_before = cumE[wave][si - 1];
+                    split_owned(seg_lo - gone_before, (seg_hi - seg_lo) - gone_own, lad[si - 1], true,
+                                seg_lo - out_before, 0u, false);
+                    gone_own = out_own;
+                    gone_before = out_before;
                     cnt = left;
                 }
                 eval_slot(si);
@@ -1119,13 +1107,16 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
         if (nested) {
 /* ---- every phase is cut out of the LDS copy of the instance ---- */
             const uint32_t m_max = G.m[G.n_m - 1];
-            uint32_t cnt = 0; /* jobs of the levels up to m_max: the largest merged phase */
-            for (uint32_t l = 0; l <= m_max; l++)
-                cnt += totE[l];
-            if (cnt < n) {
-                if (cnt > 0)
-                    split_front(n, lad[m_max]);
-                split_tail(cnt);
+            /* Of this wavefront's segment of the input, cumE[wave][g] jobs are of the levels up to g,
+             * and cumL[wave][g] holds the same count summed over the wavefronts before it: that is
+             * where its share of the merged phase of level g begins, and how long it is. */
+            const uint32_t cnt0 = upE[m_max]; /* jobs of the levels up to m_max: the largest merged phase */
+            if (cnt0 < n) {
+                const uint32_t own = cumE[wave][m_max], before = cumL[wave][m_max];
+                const uint32_t tail_lo = cnt0 + (seg_lo - before);
+                if (cnt0 > 0)
+                    split_owned(seg_lo, seg_hi - seg_lo, lad[m_max], false, before, tail_lo, true);
+                split_tail_owned(tail_lo, (seg_hi - seg_lo) - own, cumL[wave]);
             }
             int mi = (int)G.n_m - 1;
             for (uint32_t g = m_max;; g--) {
@@ -1141,10 +1132,10 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                 }
                 if (g == m_min)
                     break;
-                const uint32_t below = cnt - totE[g];
-                if (totE[g] > 0 && below > 0)
-                    split_front(cnt, lad[g - 1]); /* level g's jobs move behind the lower levels' */
-                cnt = below;
+                const uint32_t below = upE[g - 1u];
+                if (totE[g] > 0 && below > 0) /* level g's jobs move behind the lower levels', into the level's own slot */
+                    split_owned(cumL[wave][g], cumE[wave][g], lad[g - 1u], false, cumL[wave][g - 1u],
+                                below + (cumL[wave][g] - cumL[wave][g - 1u]), true);
             }
             for (int si = (int)m_min + 1; si < kLevels; si++)
                 eval_slot(si);
