@@ -131,6 +131,29 @@ __device__ __forceinline__ void get_entry(const uint32_t *buf, uint32_t n_cap, u
     }
 }
 
+/* The same for an entry whose first word has been read already (a loop that reads two entries
+ * with one LDS instruction and then works through them). */
+template <bool PACKED>
+__device__ __forceinline__ void entry_of_word(uint32_t w, const uint32_t *buf, uint32_t n_cap, uint32_t pos,
+                                              uint32_t &d, bool &done, uint32_t &s, const EntryFmt &F,
+                                              uint32_t tau)
+{
+    if (PACKED) {
+        d = w & ((1u << F.dbits) - 1u);
+        if (F.raw) {
+            done = d <= tau;
+            d = done ? d : tau;
+        } else {
+            done = F.all_done || ((w >> F.dbits) & 1u);
+        }
+        s = (w >> F.sshift) + F.s_add;
+    } else {
+        d = w & 0x7fffffffu;
+        done = w >> 31;
+        s = buf[n_cap + pos];
+    }
+}
+
 /* An end event: one run less, and its weight w = s + 1 - start taken out: -(2^32 + w), as
  * this constant plus the sign-extended -w. */
 constexpr unsigned long long kEndOne = 0xffffffff00000000ull;
@@ -240,10 +263,10 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
                 const uint32_t q_step = kvs_div(sl.tau, sc.div);
                 const uint32_t r_step = sl.tau - q_step * sc.k;
                 uint32_t cur = f - t_s, accS = 0, accN = 0;
-                for (uint32_t j = 0; j < cnt; j++) {
+                auto one = [&](uint32_t w, uint32_t at) {
                     uint32_t d, s;
                     bool done;
-                    get_entry<PACKED>(buf, n_cap, sl.off + rb + j, d, done, s, s_scalar, F, sl.tau);
+                    entry_of_word<PACKED>(w, buf, n_cap, at, d, done, s, F, sl.tau);
                     const uint32_t st = f - t_s; /* in [0, len) */
                     if (st != cur) { /* cur is the round of the run before: something is held */
                         atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
@@ -260,7 +283,18 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
                     const bool over = rem >= sc.k;
                     rem -= over ? sc.k : 0u;
                     f += q_step + (over ? 1u : 0u);
+                };
+                const uint32_t pos = sl.off + rb;
+                uint32_t j = 0;
+                for (; j + 3u < cnt; j += 4u) { /* four entries per round trip to LDS */
+                    const uint32_t w0 = buf[pos + j], w1 = buf[pos + j + 1u], w2 = buf[pos + j + 2u], w3 = buf[pos + j + 3u];
+                    one(w0, pos + j);
+                    one(w1, pos + j + 1u);
+                    one(w2, pos + j + 2u);
+                    one(w3, pos + j + 3u);
                 }
+                for (; j < cnt; j++)
+                    one(buf[pos + j], pos + j);
                 if (accN)
                     atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
             } else {
@@ -276,15 +310,25 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
                     uint32_t seg = sc.k - inb;
                     seg = seg < left ? seg : left;
                     uint32_t accS = 0;
-                    for (uint32_t j = 0; j < seg; j++) {
+                    auto one = [&](uint32_t w, uint32_t at) {
                         uint32_t d, s;
                         bool done;
-                        get_entry<PACKED>(buf, n_cap, pos + j, d, done, s, s_scalar, F, sl.tau);
+                        entry_of_word<PACKED>(w, buf, n_cap, at, d, done, s, F, sl.tau);
                         accS += s + 1u;
                         const uint32_t en = st + d;
                         if (en < len)
                             atomicAdd(&ev[en], W::end((int32_t)((s + 1u) - st)));
+                    };
+                    uint32_t j = 0;
+                    for (; j + 3u < seg; j += 4u) { /* four entries per round trip to LDS */
+                        const uint32_t w0 = buf[pos + j], w1 = buf[pos + j + 1u], w2 = buf[pos + j + 2u], w3 = buf[pos + j + 3u];
+                        one(w0, pos + j);
+                        one(w1, pos + j + 1u);
+                        one(w2, pos + j + 2u);
+                        one(w3, pos + j + 3u);
                     }
+                    for (; j < seg; j++)
+                        one(buf[pos + j], pos + j);
                     atomicAdd(&ev[st], W::starts(seg, (int32_t)(accS - __umul24(seg, st))));
                     pos += seg;
                     left -= seg;
@@ -311,10 +355,10 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
             const uint32_t r_step = sps ? sl.tau - q_step * sc.k : 1u;
             const uint32_t wrap = sps ? 1u : sl.tau;
             uint32_t cur = 0, accS = 0, accN = 0;
-            for (uint32_t j = 0; j < cnt; j++) {
+            auto one = [&](uint32_t w, uint32_t at) {
                 uint32_t d, s;
                 bool done;
-                get_entry<PACKED>(buf, n_cap, sl.off + rb + j, d, done, s, s_scalar, F, sl.tau);
+                entry_of_word<PACKED>(w, buf, n_cap, at, d, done, s, F, sl.tau);
                 const uint32_t st = f - t_s; /* in [0, len) */
                 if (st != cur && accN) {
                     atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
@@ -333,7 +377,18 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
                 const bool over = rem >= sc.k;
                 rem -= over ? sc.k : 0u;
                 f += q_step + (over ? wrap : 0u);
+            };
+            const uint32_t pos = sl.off + rb;
+            uint32_t j = 0;
+            for (; j + 3u < cnt; j += 4u) { /* four entries per round trip to LDS */
+                const uint32_t w0 = buf[pos + j], w1 = buf[pos + j + 1u], w2 = buf[pos + j + 2u], w3 = buf[pos + j + 3u];
+                one(w0, pos + j);
+                one(w1, pos + j + 1u);
+                one(w2, pos + j + 2u);
+                one(w3, pos + j + 3u);
             }
+            for (; j < cnt; j++)
+                one(buf[pos + j], pos + j);
             if (accN)
                 atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
         }
