@@ -314,7 +314,8 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
         uint32_t mxO = 0, mxS = 0, mxG = 0;
         uint32_t badbits = 0;
         const bool want_e = with_estimates;
-        auto account = [&](const RawJob &raw, uint32_t i) {
+        /* first part of a job's accounting; returns the level that keeps its prompt, and the prompt */
+        auto account_a = [&](const RawJob &raw, uint32_t i, uint32_t &g_out, uint32_t &s_out) {
             const JobView v = view_job<EXPLICIT>(raw, J, G, lad, mode, with_estimates);
             badbits |= v.bad;
             if (mode != MODE_SINGLE || v.go == 0)
@@ -335,13 +336,35 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                 atomicAdd(&myL[v.gb], 1u);
             else if (!PACKED && !one_phase_each)
                 atomicAdd(&cumL[wave][v.gb], 1u);
-            if (per_job_s) { /* the maxima settle after a few jobs; then this only reads */
-                if (v.s > sMaxEnter[g_max])
-                    atomicMax(&sMaxEnter[g_max], v.s);
-                if (!NESTED && !ALIVE) /* else one level says it all: the only one (NESTED), the last one (ALIVE) */
-                    for (uint32_t l = v.ga; l <= v.gb; l++)
-                        if (v.s > sMaxPart[l])
-                            atomicMax(&sMaxPart[l], v.s);
+            if (per_job_s && !NESTED && !ALIVE) /* else one level says it all: the only one (NESTED), the last one (ALIVE) */
+                for (uint32_t l = v.ga; l <= v.gb; l++)
+                    if (v.s > sMaxPart[l]) /* the maxima settle after a few jobs; then this only reads */
+                        atomicMax(&sMaxPart[l], v.s);
+            g_out = g_max;
+            s_out = v.s;
+        };
+        auto account = [&](const RawJob &raw, uint32_t i) {
+            uint32_t g, s;
+            account_a(raw, i, g, s);
+            if (per_job_s && s > sMaxEnter[g]) /* settles after a few jobs; then this only reads */
+                atomicMax(&sMaxEnter[g], s);
+        };
+        /* four jobs: their four looks at the prompt maxima travel to LDS together */
+        auto account4 = [&](const RawJob &a, const RawJob &b, const RawJob &c, const RawJob &d, uint32_t i) {
+            uint32_t g[4], s[4];
+            account_a(a, i, g[0], s[0]);
+            account_a(b, i + 1u, g[1], s[1]);
+            account_a(c, i + 2u, g[2], s[2]);
+            account_a(d, i + 3u, g[3], s[3]);
+            if (per_job_s) {
+                uint32_t cur[4];
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    cur[q] = sMaxEnter[g[q]];
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    if (s[q] > cur[q])
+                        atomicMax(&sMaxEnter[g[q]], s[q]);
             }
         };
         if (J.vec4) {
@@ -376,10 +399,8 @@ __device__ __forceinline__ void sweep_instance(const JobsDev &J, const GroupArg 
                 for (uint32_t dch = 0; dch < kDeep; dch++) {
                     const uint32_t i = base + 256u * dch + 4u * (uint32_t)lane;
                     if (i < seg_hi) {
-                        account(RawJob{q[dch].o.x, q[dch].s.x, q[dch].e.x}, i);
-                        account(RawJob{q[dch].o.y, q[dch].s.y, q[dch].e.y}, i + 1);
-                        account(RawJob{q[dch].o.z, q[dch].s.z, q[dch].e.z}, i + 2);
-                        account(RawJob{q[dch].o.w, q[dch].s.w, q[dch].e.w}, i + 3);
+                        account4(RawJob{q[dch].o.x, q[dch].s.x, q[dch].e.x}, RawJob{q[dch].o.y, q[dch].s.y, q[dch].e.y},
+                                 RawJob{q[dch].o.z, q[dch].s.z, q[dch].e.z}, RawJob{q[dch].o.w, q[dch].s.w, q[dch].e.w}, i);
                     }
                 }
             }
