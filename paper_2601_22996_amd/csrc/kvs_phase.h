@@ -495,14 +495,25 @@ __device__ __forceinline__ void eval_thin(const Slot &sl, const Sched &sc, bool 
     const uint32_t q_lo = ranks_before(t + 1u > sl.tau ? t + 1u - sl.tau : 0u, sl, sc, sps);
     const uint32_t q_hi = ranks_before(t + 1u, sl, sc, sps);
     uint32_t occ = 0;
-    for (uint32_t q = q_lo; q < q_hi; q++) {
+    auto other = [&](uint32_t word, uint32_t q) {
         uint32_t dq, sq;
         bool doneq;
-        get_entry<PACKED>(buf, n_cap, sl.off + q, dq, doneq, sq, s_scalar, F, sl.tau);
+        entry_of_word<PACKED>(word, buf, n_cap, sl.off + q, dq, doneq, sq, F, sl.tau);
         const uint32_t fq = start_offset(q, sl.tau, sc, sps);
         if (fq <= t && t < fq + dq)
             occ += sq + 1u + (t - fq);
+    };
+    uint32_t q = q_lo;
+    for (; q + 3u < q_hi; q += 4u) { /* four entries per round trip to LDS */
+        const uint32_t w0 = buf[sl.off + q], w1 = buf[sl.off + q + 1u], w2 = buf[sl.off + q + 2u],
+                       w3 = buf[sl.off + q + 3u];
+        other(w0, q);
+        other(w1, q + 1u);
+        other(w2, q + 2u);
+        other(w3, q + 3u);
     }
+    for (; q < q_hi; q++)
+        other(buf[sl.off + q], q);
     if ((int32_t)occ > pk)
         pk = (int32_t)occ;
 }
