@@ -14,6 +14,7 @@
 #include <type_traits>
 
 #include "kvs_math.h"
+#include "kvs_wave.h"
 #include "kvsched.h"
 #include "kvsched_test.h"
 
@@ -28,6 +29,7 @@ struct BJobs {
     const int32_t *o, *s;
     int32_t n_inst, n_jobs;
     uint32_t s_scalar;
+    uint32_t mant_bits; /* buckets of the area ranking: 2^mant_bits per power of two (0: sort instead) */
     uint64_t M;
 };
 
@@ -242,12 +244,28 @@ __device__ uint64_t ranked_sum(KT *key, uint32_t n, TwoRuns runs, uint32_t tid)
 
 constexpr int64_t kAreaPending = INT64_MIN; /* internal: areas too wide for 32-bit keys, left to the second launch */
 
+/* ---- ranks by buckets ---- */
+
+/* Bucket of a key a >= 1: the position of its leading bit and the mb bits below it; keys below
+ * 2^mb have a bucket each.  Non-decreasing in a, so all keys of a lower bucket are smaller. */
+__device__ __forceinline__ uint32_t bucket_of(uint32_t a, uint32_t mb)
+{
+    const uint32_t t = 31u - (uint32_t)__clz((int)a);
+    return t < mb ? a : (((t - mb + 1u) << mb) | ((a >> (t - mb)) & ((1u << mb) - 1u)));
+}
+__host__ __device__ inline uint32_t bucket_count(uint32_t mb) { return (33u - mb) << mb; }
+
+/* A bucket with more keys than this sends the instance to the sort: every key is compared with
+ * all keys of its bucket, which is cheap only while buckets are small. */
+constexpr uint32_t kBucketLimit = 128;
+
 /*
  * One workgroup per instance (T threads, n_jobs <= 16 T).  LDS holds only the sort keys --
  * 32-bit in the first launch
  * (WIDE = false), which leaves an instance whose largest area needs more to the second launch
  * with 64-bit keys (WIDE = true, twice the LDS, one workgroup per compute unit instead of two)
- * -- and per wavefront one histogram of the levels of the current base.
+ * -- beside the bucket table of the first launch, and per wavefront one histogram of the levels
+ * of the current base.
  *
  * 1. load and check the jobs, find the largest area; the level histogram of the first base is
  *    counted on the way;
@@ -258,9 +276,11 @@ constexpr int64_t kAreaPending = INT64_MIN; /* internal: areas too wide for 32-b
  *    take the classes of one point: each computes k_p, Q_p and floor(n_p tau_p / k_p) + tau_p,
  *    a prefix sum over the lanes gives S_p, a sum n_p S_p + Q_p the bound (Step 3 of the
  *    analysis of GBA);
- * 3. the areas (jobs read again, from cache) sorted as one or two runs (bitonic, 16 keys per thread, up to four stages per
- *    pass over LDS), sum of (n - j) * area_j over the ascending sequence j = 0 .. n-1 (Step 1,
- *    proof of the lower bound).
+ * 3. the sum of (n - j) * area_j over the ascending sequence j = 0 .. n-1 (Step 1, proof of the
+ *    lower bound).  First launch: the areas (jobs read again, from cache) are dealt into buckets
+ *    by their leading bits and a key's place is its bucket's start plus its rank among the keys
+ *    of its bucket; an instance with a crowded bucket, and the second launch, sort the areas as
+ *    one or two runs instead (bitonic, 16 keys per thread, up to four stages per pass over LDS).
  */
 template <int T, bool WIDE>
 __global__ __launch_bounds__(T, (T == 1024 && !WIDE) ? 8 : 1) void kvs_bounds_kernel(BJobs J, BPoints P, int64_t *upper,
@@ -424,6 +444,109 @@ __global__ __launch_bounds__(T, (T == 1024 && !WIDE) ? 8 : 1) void kvs_bounds_ke
         if (tid == 0)
             area_num[inst] = kAreaPending;
         return;
+    }
+    if (!WIDE && J.mant_bits != 0) {
+        /* 3a. The place of a key in the ascending sequence without sorting everything: the keys
+         * are dealt into buckets by their leading bits (a counting sort: count, running sums,
+         * scatter; inside a bucket in any order), and a key's place is where its bucket begins
+         * plus the number of keys of its bucket that are smaller, or equal and in front of it. */
+        const uint32_t mb = J.mant_bits, nb = bucket_count(mb);
+        uint32_t *const srt = reinterpret_cast<uint32_t *>(lds_raw); /* n keys in bucket order */
+        uint32_t *const cntb = srt + n;                              /* nb + 1 counts, then starts */
+        __shared__ uint32_t scan_w[NW];
+        __shared__ uint32_t biggest;
+        for (uint32_t i = tid; i <= nb; i += T)
+            cntb[i] = 0;
+        if (tid == 0)
+            biggest = 0;
+        __syncthreads();
+        uint32_t my_a[16], my_bp[16]; /* this thread's keys, and bucket << 16 | place in the bucket */
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const uint32_t i = tid + (uint32_t)k * T;
+            my_a[k] = 0;
+            my_bp[k] = 0;
+            if (i < n) { /* the jobs again, from cache */
+                uint32_t o, s;
+                read_job(i, o, s);
+                const uint32_t a = (uint32_t)area_of(o, s);
+                const uint32_t b = bucket_of(a, mb);
+                my_a[k] = a;
+                my_bp[k] = (b << 16) | atomicAdd(&cntb[b], 1u);
+            }
+        }
+        __syncthreads();
+        /* running sums over the buckets: every thread takes a stretch of them */
+        {
+            const uint32_t per = (nb + T) / T; /* covers the nb + 1 entries */
+            const uint32_t lo = tid * per, hi = lo + per < nb + 1u ? lo + per : nb + 1u;
+            uint32_t sum = 0, mx = 0;
+            for (uint32_t b = lo; b < hi; b++) {
+                const uint32_t c = cntb[b];
+                sum += c;
+                mx = c > mx ? c : mx;
+            }
+            const uint32_t incl = (uint32_t)wave_prefix_add((int32_t)sum);
+            if (lane == kWave - 1)
+                scan_w[wave] = incl;
+            mx = (uint32_t)wave_max_nonneg((int32_t)mx);
+            if (lane == 0)
+                atomicMax(&biggest, mx);
+            __syncthreads();
+            uint32_t before = incl - sum;
+            for (uint32_t w = 0; w < wave; w++)
+                before += scan_w[w];
+            for (uint32_t b = lo; b < hi; b++) {
+                const uint32_t c = cntb[b];
+                cntb[b] = before;
+                before += c;
+            }
+        }
+        __syncthreads();
+        if (biggest <= kBucketLimit) {
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                const uint32_t i = tid + (uint32_t)k * T;
+                if (i < n)
+                    srt[cntb[my_bp[k] >> 16] + (my_bp[k] & 0xffffu)] = my_a[k];
+            }
+            __syncthreads();
+            /* consecutive lanes take consecutive places, so a wavefront's lanes look at the same
+             * few buckets */
+            uint64_t sum = 0;
+            for (uint32_t p = tid; p < n; p += T) {
+                const uint32_t a = srt[p];
+                const uint32_t b = bucket_of(a, mb);
+                const uint32_t lo = cntb[b], hi = cntb[b + 1u];
+                uint32_t r = 0;
+                auto cmp = [&](uint32_t v, uint32_t q) { r += (v < a || (v == a && q < p)) ? 1u : 0u; };
+                uint32_t q = lo;
+                for (; q + 3u < hi; q += 4u) { /* four keys per round trip to LDS */
+                    const uint32_t v0 = srt[q], v1 = srt[q + 1u], v2 = srt[q + 2u], v3 = srt[q + 3u];
+                    cmp(v0, q);
+                    cmp(v1, q + 1u);
+                    cmp(v2, q + 2u);
+                    cmp(v3, q + 3u);
+                }
+                for (; q < hi; q++)
+                    cmp(srt[q], q);
+                sum += (uint64_t)(n - (lo + r)) * a;
+            }
+            sum = wave_sum64(sum);
+            if (lane == 0)
+                red[wave] = sum;
+            __syncthreads();
+            if (tid == 0) {
+                uint64_t tot = 0;
+                for (int w = 0; w < NW; w++)
+                    tot += red[w];
+                const uint64_t tri = (uint64_t)n * (n + 1u) / 2u;
+                const bool wide = __umul64hi(tri, amax) != 0 || tri * amax >= (1ull << 63);
+                area_num[inst] = wide ? -1 : (int64_t)tot;
+            }
+            return;
+        }
+        __syncthreads(); /* a crowded bucket: the sort below takes over the same memory */
     }
     const TwoRuns runs = split_runs(n);
     const uint32_t b0 = slot_of(runs.a); /* where run B begins */
@@ -677,6 +800,7 @@ BJobs to_bjobs(const kvs_jobs_t *jobs)
     J.n_inst = jobs->n_instances;
     J.n_jobs = jobs->n_jobs;
     J.s_scalar = jobs->s ? 0u : (uint32_t)jobs->s_scalar;
+    J.mant_bits = 0;
     J.M = (uint64_t)jobs->M;
     return J;
 }
@@ -721,16 +845,23 @@ int32_t kvs_flow_bounds(const kvs_jobs_t *jobs, const int32_t *tau0, int32_t n_p
     const uint32_t n = (uint32_t)jobs->n_jobs;
     const TwoRuns runs = split_runs(n);
     const size_t slots = (size_t)runs.a + runs.a / 16 + runs.b + runs.b / 16 + 1;
+    /* the first launch ranks by buckets where it can: the keys and the bucket table beside them;
+     * 256 buckets per power of two while two workgroups of the largest kind still fit a compute
+     * unit's LDS, else 128 */
+    BJobs J32 = to_bjobs(jobs);
+    J32.mant_bits = (sizeof(uint32_t) * ((size_t)n + bucket_count(8) + 1) <= 72 * 1024) ? 8u : 7u;
+    const size_t lds_b = sizeof(uint32_t) * ((size_t)n + bucket_count(J32.mant_bits) + 1);
+    const size_t lds64 = sizeof(uint64_t) * slots;
+    const size_t lds32 = sizeof(uint32_t) * slots > lds_b ? sizeof(uint32_t) * slots : lds_b;
     hipStream_t st = static_cast<hipStream_t>(stream);
     auto launch = [&](auto kern, int threads, size_t lds) -> int32_t {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return KVS_EHIP;
         hipLaunchKernelGGL(kern, dim3((uint32_t)jobs->n_instances), dim3(threads), lds, st,
-                           to_bjobs(jobs), P, n_pts > 0 ? upper_gba : nullptr, area_lb_num);
+                           J32, P, n_pts > 0 ? upper_gba : nullptr, area_lb_num);
         return hipGetLastError() == hipSuccess ? KVS_OK : KVS_EHIP;
     };
-    const size_t lds32 = sizeof(uint32_t) * slots, lds64 = sizeof(uint64_t) * slots;
     rc = n > 4096   ? launch(kvs_bounds_kernel<1024, false>, 1024, lds32)
          : n > 1024 ? launch(kvs_bounds_kernel<256, false>, 256, lds32)
                     : launch(kvs_bounds_kernel<64, false>, 64, lds32);

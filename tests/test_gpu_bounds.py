@@ -72,6 +72,27 @@ def test_random_instances(K, n):
     assert np.array_equal(ar, war), np.argwhere(ar != war)[:4]
 
 
+@pytest.mark.parametrize("n", [600, 5000])
+def test_area_bound_with_crowded_buckets(K, n):
+    """The area bound ranks keys inside buckets of leading bits and falls back on a full sort when
+    a bucket is crowded (more than 128 keys): instances just below and just above that, with ties
+    inside a bucket and neighbouring values that share one, against the oracle."""
+    rng = np.random.default_rng(77 + n)
+    rows = []
+    for crowd in (127, 128, 129, 400):
+        o = rng.integers(1, 2000, n).astype(np.int32)
+        s = rng.integers(0, 300, n).astype(np.int32)
+        at = rng.choice(n, crowd, replace=False)
+        o[at] = 1                              # areas s + 1 = 5001 and 5002: one bucket at either
+        s[at] = rng.integers(5000, 5002, crowd)  # resolution (16 or 32 values wide there), many ties
+        rows.append((o, s))
+    o = np.stack([r[0] for r in rows])
+    s = np.stack([r[1] for r in rows])
+    _, ar = gpu_bounds(K, o, s, 1 << 20, [1])
+    _, war = oracle_bounds(o, s, 1 << 20, [1])
+    assert np.array_equal(ar, war), (ar, war)
+
+
 def test_64_points_and_outputs_optional(K):
     rng = np.random.default_rng(4)
     o = np.minimum(rng.geometric(1 / 100, (5, 700)), 5000).astype(np.int32)
