@@ -1972,7 +1972,7 @@ const char *kvs_strerror(int32_t status)
     }
 }
 
-int32_t kvs_version(void) { return 500; }
+int32_t kvs_version(void) { return 600; }
 
 /* Host evaluation of the kernels' integer helpers, for the host-side tests (kvsched_test.h). */
 uint32_t kvs_host_class_index(uint32_t x, uint32_t tau0)
