@@ -248,119 +248,25 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
         const uint32_t blk = ((r2 - r1 + 63u) >> 6) | 1u;
         const uint32_t rb = r1 + (uint32_t)lane * blk;
         const uint32_t cnt = rb < r2 ? (r2 - rb < blk ? r2 - rb : blk) : 0u;
-        if (F.all_done) {
-            /* every run completes (one instantiation's constant): nothing is summed over the
-             * runs but the window's events, and each subroutine has a loop of its own */
-            if (sps) {
-                /* inside a block the start offset is carried from rank to rank (quotient and
-                 * remainder of r tau / k) instead of divided out each time: per rank the remainder
-                 * grows by tau mod k, and the offset by floor(tau / k) and one more when it wraps */
-                uint32_t f = 0, rem = 0;
-                if (cnt) {
-                    f = kvs_div(rb * sl.tau, sc.div);
-                    rem = rb * sl.tau - f * sc.k;
-                }
-                const uint32_t q_step = kvs_div(sl.tau, sc.div);
-                const uint32_t r_step = sl.tau - q_step * sc.k;
-                uint32_t cur = f - t_s, accS = 0, accN = 0;
-                auto one = [&](uint32_t w, uint32_t at) {
-                    uint32_t d, s;
-                    bool done;
-                    entry_of_word<PACKED>(w, buf, n_cap, at, d, done, s, F, sl.tau);
-                    const uint32_t st = f - t_s; /* in [0, len) */
-                    if (st != cur) { /* cur is the round of the run before: something is held */
-                        atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
-                        accS = 0;
-                        accN = 0;
-                    }
-                    cur = st;
-                    accS += s + 1u;
-                    accN += 1u;
-                    const uint32_t en = st + d;
-                    if (en < len)
-                        atomicAdd(&ev[en], W::end((int32_t)((s + 1u) - st)));
-                    rem += r_step;
-                    const bool over = rem >= sc.k;
-                    rem -= over ? sc.k : 0u;
-                    f += q_step + (over ? 1u : 0u);
-                };
-                const uint32_t pos = sl.off + rb;
-                uint32_t j = 0;
-                for (; j + 3u < cnt; j += 4u) { /* four entries per round trip to LDS */
-                    const uint32_t w0 = buf[pos + j], w1 = buf[pos + j + 1u], w2 = buf[pos + j + 2u], w3 = buf[pos + j + 3u];
-                    one(w0, pos + j);
-                    one(w1, pos + j + 1u);
-                    one(w2, pos + j + 2u);
-                    one(w3, pos + j + 3u);
-                }
-                for (; j < cnt; j++)
-                    one(buf[pos + j], pos + j);
-                if (accN)
-                    atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
-            } else {
-                /* SimS: the runs of a batch start together, so a block is gone through batch by
-                 * batch with the round fixed, and each stretch adds its start events once */
-                uint32_t left = cnt, pos = sl.off + rb, inb = 0, st = 0;
-                if (cnt) {
-                    const uint32_t b = kvs_div(rb, sc.div);
-                    inb = rb - b * sc.k;       /* place of the first rank in its batch */
-                    st = b * sl.tau - t_s;     /* in [0, len) */
-                }
-                while (left) {
-                    uint32_t seg = sc.k - inb;
-                    seg = seg < left ? seg : left;
-                    uint32_t accS = 0;
-                    auto one = [&](uint32_t w, uint32_t at) {
-                        uint32_t d, s;
-                        bool done;
-                        entry_of_word<PACKED>(w, buf, n_cap, at, d, done, s, F, sl.tau);
-                        accS += s + 1u;
-                        const uint32_t en = st + d;
-                        if (en < len)
-                            atomicAdd(&ev[en], W::end((int32_t)((s + 1u) - st)));
-                    };
-                    uint32_t j = 0;
-                    for (; j + 3u < seg; j += 4u) { /* four entries per round trip to LDS */
-                        const uint32_t w0 = buf[pos + j], w1 = buf[pos + j + 1u], w2 = buf[pos + j + 2u], w3 = buf[pos + j + 3u];
-                        one(w0, pos + j);
-                        one(w1, pos + j + 1u);
-                        one(w2, pos + j + 2u);
-                        one(w3, pos + j + 3u);
-                    }
-                    for (; j < seg; j++)
-                        one(buf[pos + j], pos + j);
-                    atomicAdd(&ev[st], W::starts(seg, (int32_t)(accS - __umul24(seg, st))));
-                    pos += seg;
-                    left -= seg;
-                    inb = 0;
-                    st += sl.tau;
-                }
-            }
-        } else {
-            /* the start offset is carried from rank to rank (quotient and remainder of
-             * r tau / k, or of r / k) instead of divided out each time: per rank SPS adds tau to
-             * the remainder modulo k, SimS adds 1 modulo k (tau rounds per wrap) */
+        /* each subroutine has a loop of its own over the runs that start in the slab */
+        if (sps) {
+            /* inside a block the start offset is carried from rank to rank (quotient and
+             * remainder of r tau / k) instead of divided out each time: per rank the remainder
+             * grows by tau mod k, and the offset by floor(tau / k) and one more when it wraps */
             uint32_t f = 0, rem = 0;
             if (cnt) {
-                if (sps) {
-                    f = kvs_div(rb * sl.tau, sc.div);
-                    rem = rb * sl.tau - f * sc.k;
-                } else {
-                    const uint32_t b = kvs_div(rb, sc.div);
-                    f = b * sl.tau;
-                    rem = rb - b * sc.k;
-                }
+                f = kvs_div(rb * sl.tau, sc.div);
+                rem = rb * sl.tau - f * sc.k;
             }
-            const uint32_t q_step = sps ? kvs_div(sl.tau, sc.div) : 0u;
-            const uint32_t r_step = sps ? sl.tau - q_step * sc.k : 1u;
-            const uint32_t wrap = sps ? 1u : sl.tau;
-            uint32_t cur = 0, accS = 0, accN = 0;
+            const uint32_t q_step = kvs_div(sl.tau, sc.div);
+            const uint32_t r_step = sl.tau - q_step * sc.k;
+            uint32_t cur = f - t_s, accS = 0, accN = 0;
             auto one = [&](uint32_t w, uint32_t at) {
                 uint32_t d, s;
                 bool done;
                 entry_of_word<PACKED>(w, buf, n_cap, at, d, done, s, F, sl.tau);
                 const uint32_t st = f - t_s; /* in [0, len) */
-                if (st != cur && accN) {
+                if (st != cur) { /* cur is the round of the run before: something is held */
                     atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
                     accS = 0;
                     accN = 0;
@@ -371,12 +277,14 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
                 const uint32_t en = st + d;
                 if (en < len)
                     atomicAdd(&ev[en], W::end((int32_t)((s + 1u) - st)));
-                sum_st += done ? st : 0u;
-                n_done += done ? 1u : 0u;
+                if (!F.all_done) { /* else the caller has the sum of the start offsets in closed form */
+                    sum_st += done ? st : 0u;
+                    n_done += done ? 1u : 0u;
+                }
                 rem += r_step;
                 const bool over = rem >= sc.k;
                 rem -= over ? sc.k : 0u;
-                f += q_step + (over ? wrap : 0u);
+                f += q_step + (over ? 1u : 0u);
             };
             const uint32_t pos = sl.off + rb;
             uint32_t j = 0;
@@ -391,6 +299,50 @@ __device__ __forceinline__ void eval_slab(const Slot &sl, const Sched &sc, bool 
                 one(buf[pos + j], pos + j);
             if (accN)
                 atomicAdd(&ev[cur], W::starts(accN, (int32_t)(accS - __umul24(accN, cur))));
+        } else {
+            /* SimS: the runs of a batch start together, so a block is gone through batch by
+             * batch with the round fixed, and each stretch adds its start events once */
+            uint32_t left = cnt, pos = sl.off + rb, inb = 0, st = 0;
+            if (cnt) {
+                const uint32_t b = kvs_div(rb, sc.div);
+                inb = rb - b * sc.k;       /* place of the first rank in its batch */
+                st = b * sl.tau - t_s;     /* in [0, len) */
+            }
+            while (left) {
+                uint32_t seg = sc.k - inb;
+                seg = seg < left ? seg : left;
+                uint32_t accS = 0, seg_done = 0;
+                auto one = [&](uint32_t w, uint32_t at) {
+                    uint32_t d, s;
+                    bool done;
+                    entry_of_word<PACKED>(w, buf, n_cap, at, d, done, s, F, sl.tau);
+                    accS += s + 1u;
+                    const uint32_t en = st + d;
+                    if (en < len)
+                        atomicAdd(&ev[en], W::end((int32_t)((s + 1u) - st)));
+                    if (!F.all_done)
+                        seg_done += done ? 1u : 0u;
+                };
+                uint32_t j = 0;
+                for (; j + 3u < seg; j += 4u) { /* four entries per round trip to LDS */
+                    const uint32_t w0 = buf[pos + j], w1 = buf[pos + j + 1u], w2 = buf[pos + j + 2u], w3 = buf[pos + j + 3u];
+                    one(w0, pos + j);
+                    one(w1, pos + j + 1u);
+                    one(w2, pos + j + 2u);
+                    one(w3, pos + j + 3u);
+                }
+                for (; j < seg; j++)
+                    one(buf[pos + j], pos + j);
+                atomicAdd(&ev[st], W::starts(seg, (int32_t)(accS - __umul24(seg, st))));
+                if (!F.all_done) { /* st < 2^10, a stretch is a part of a lane's block */
+                    sum_st += __umul24(seg_done, st);
+                    n_done += seg_done;
+                }
+                pos += seg;
+                left -= seg;
+                inb = 0;
+                st += sl.tau;
+            }
         }
     }
     if (!F.all_done) /* else the caller has the sum in closed form */
